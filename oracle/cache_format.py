@@ -1,0 +1,93 @@
+"""Packed key-cache page layout (oracle's own write-up; test infrastructure only).
+
+The paper fixes what is stored per pair -- an r-bit radius code, a t-bit angle
+code, and per group a 16-bit scale and a 16-bit zero-point per pair (Section
+3.2; Appendix B.1 for the 16-bit parameters) -- but not the byte layout.  The
+layout below is this project's; the HIP library documents the same layout in
+its public header and the two write-ups share no code.
+
+  symbol      = (angle_code << r) | radius_code                    w = r + t bits
+  unit        = 16 consecutive pairs' symbols of one token, as a little-endian
+                bit string: symbol k occupies bits [k*w, (k+1)*w); bit i of the
+                string is bit (i % 8) of byte (i // 8).  A unit is 2*w bytes.
+  codes page  = [kv_head][pair_block = pair // 16][token_in_page][unit]
+  params page = [kv_head][pair]{fp16 scale, fp16 zero}
+  value page  = [kv_head][token_in_page][d] fp16
+
+A page holds `g` tokens (one quantization group).  Slots of a partial last
+page beyond the sequence length hold zero bytes.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+PAIRS_PER_UNIT = 16
+
+
+def unit_bytes(r_bits: int, t_bits: int) -> int:
+    return 2 * (r_bits + t_bits)
+
+
+def pack_units(a: np.ndarray, c: np.ndarray, r_bits: int, t_bits: int) -> np.ndarray:
+    """[..., 16] angle and radius codes -> [..., 2*w] bytes."""
+    w = r_bits + t_bits
+    assert a.shape[-1] == PAIRS_PER_UNIT and a.shape == c.shape
+    assert a.min(initial=0) >= 0 and a.max(initial=0) < (1 << t_bits)
+    assert c.min(initial=0) >= 0 and c.max(initial=0) < (1 << r_bits)
+    sym = (a.astype(np.int64) << r_bits) | c.astype(np.int64)
+    bits = ((sym[..., None] >> np.arange(w)) & 1).astype(np.uint8)       # [..., 16, w], LSB first
+    bits = bits.reshape(sym.shape[:-1] + (PAIRS_PER_UNIT * w,))
+    return np.packbits(bits, axis=-1, bitorder="little")
+
+
+def unpack_units(units: np.ndarray, r_bits: int, t_bits: int):
+    """[..., 2*w] bytes -> (angle codes, radius codes), each int64 [..., 16]."""
+    w = r_bits + t_bits
+    assert units.dtype == np.uint8 and units.shape[-1] == 2 * w
+    bits = np.unpackbits(units, axis=-1, bitorder="little")
+    bits = bits.reshape(units.shape[:-1] + (PAIRS_PER_UNIT, w)).astype(np.int64)
+    sym = (bits << np.arange(w)).sum(axis=-1)
+    return sym >> r_bits, sym & ((1 << r_bits) - 1)
+
+
+def pack_sequence(a, c, scale, zero, r_bits: int, t_bits: int, group_tokens: int):
+    """Pages of one sequence.
+
+    a, c: [L, H, P] codes; scale, zero: fp16 [n_pages, H, P].
+    Returns (codes uint8 [n_pages, H, P/16, g, 2w], params fp16 [n_pages, H, P, 2]).
+    """
+    L, H, P = a.shape
+    assert P % PAIRS_PER_UNIT == 0
+    g = group_tokens
+    n_pages = (L + g - 1) // g
+    nb = P // PAIRS_PER_UNIT
+    ub = unit_bytes(r_bits, t_bits)
+    codes = np.zeros((n_pages, H, nb, g, ub), np.uint8)
+    units = pack_units(a.reshape(L, H, nb, PAIRS_PER_UNIT), c.reshape(L, H, nb, PAIRS_PER_UNIT),
+                       r_bits, t_bits)                                    # [L, H, nb, ub]
+    for p in range(n_pages):
+        n0, n1 = p * g, min((p + 1) * g, L)
+        codes[p, :, :, : n1 - n0, :] = units[n0:n1].transpose(1, 2, 0, 3)
+    params = np.stack([scale.astype(np.float16), zero.astype(np.float16)], axis=-1)
+    return codes, params
+
+
+def unpack_pages(codes: np.ndarray, params: np.ndarray, length: int, r_bits: int, t_bits: int):
+    """Inverse of pack_sequence for the pages of one sequence, in order.
+
+    codes uint8 [n_pages, H, P/16, g, 2w]; params fp16 [n_pages, H, P, 2].
+    Returns (a, c) int64 [length, H, P] and (scale, zero) fp16 [n_pages, H, P].
+    """
+    n_pages, H, nb, g, _ = codes.shape
+    a, c = unpack_units(codes, r_bits, t_bits)                            # [n_pages, H, nb, g, 16]
+    a = a.transpose(0, 3, 1, 2, 4).reshape(n_pages * g, H, nb * PAIRS_PER_UNIT)[:length]
+    c = c.transpose(0, 3, 1, 2, 4).reshape(n_pages * g, H, nb * PAIRS_PER_UNIT)[:length]
+    return a, c, params[..., 0], params[..., 1]
+
+
+def codes_bytes_per_page(n_kv_heads: int, head_dim: int, r_bits: int, t_bits: int, group_tokens: int) -> int:
+    return n_kv_heads * group_tokens * (head_dim // 2) * (r_bits + t_bits) // 8
+
+
+def params_bytes_per_page(n_kv_heads: int, head_dim: int) -> int:
+    return n_kv_heads * (head_dim // 2) * 2 * 2
