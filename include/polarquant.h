@@ -1,0 +1,176 @@
+/*
+ * polarquant.h -- C ABI of libpolarquant: polar-quantized key cache for decode
+ * attention on AMD MI355X (gfx950).
+ *
+ * The library packs post-RoPE keys into radius/angle codes (paper Section 3.2)
+ * and runs one decode step of attention against the packed cache through a
+ * per-query lookup table (Section 3.3, Appendix A).  All kernels are HIP; there
+ * is no CPU fallback.
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     allocates nothing, frees nothing and keeps no state between calls except
+ *     the last HIP error code (thread-local, see pq_last_hip_error).
+ *   - Calls enqueue work on the given HIP stream (a hipStream_t passed as
+ *     void*; NULL = the default stream) and return without waiting for it.
+ *   - Every entry point returns a pq_status; argument errors are found on the
+ *     host before anything is launched.  Nothing throws or aborts.
+ *   - Inputs must be finite; for non-finite keys or queries the output is
+ *     unspecified (but no out-of-bounds access happens).
+ *
+ * Pairing.  A key (or query) of head_dim d is d/2 pairs; pair j is the two
+ * elements (j, j + d/2) that rotate-half RoPE turns together (footnote 2 of
+ * Section 3.1).  x = element j, y = element j + d/2.
+ *
+ * What is stored per pair (Section 3.2, with a uniform angle grid)
+ *   radius code c = Clamp(floor((rho - z) / s), 0, 2^r - 1),  rho = sqrt(x^2 + y^2) in fp32,
+ *       z = min and s = (max - min) / 2^r of rho over the tokens of the pair's
+ *       group (= page), both rounded to fp16 and used as rounded; c = 0 if s == 0
+ *   angle code  a = Clamp(floor((atan2(y, x) + pi) * 2^t / (2 pi)), 0, 2^t - 1);
+ *       bins are half-open arcs of the uniform grid over [-pi, pi); x = y = 0 -> 2^(t-1)
+ *   reconstruction rho~ = (c + 1/2) s + z,  theta~ = -pi + (a + 1/2) 2 pi / 2^t
+ *
+ * Packed layout (all little-endian).  A page holds group_tokens (g) tokens of
+ * every KV head.  P = d/2, w = r + t.
+ *   codes pool  : [page][kv_head][pair_block = P/16][token g][unit 2*w bytes]
+ *                 unit = the 16 symbols of pairs 16*block .. 16*block+15 of one
+ *                 token as a bit string; symbol k = (a << r) | c sits in bits
+ *                 [k*w, (k+1)*w); bit i of the string = bit (i % 8) of byte (i / 8).
+ *                 For r = t = 4 byte k of a unit is simply (a_k << 4) | c_k.
+ *   params pool : [page][kv_head][pair P]{fp16 s, fp16 z}
+ *   value pool  : [page][kv_head][token g][d] fp16        (values stay fp16, Section 4.1)
+ * Slots of a sequence's last page beyond its length hold zero bytes in the
+ * codes pool; their values are never read.
+ */
+#ifndef POLARQUANT_H
+#define POLARQUANT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PQ_OK = 0,
+  PQ_ERR_INVALID_ARG = -1,   /* null pointer, negative size, inconsistent shapes */
+  PQ_ERR_UNSUPPORTED = -2,   /* a layout this build has no kernel for */
+  PQ_ERR_WORKSPACE = -3,     /* workspace missing, misaligned or too small */
+  PQ_ERR_HIP = -4            /* a HIP call failed; see pq_last_hip_error() */
+} pq_status;
+
+typedef enum { PQ_F16 = 0, PQ_F32 = 1 } pq_dtype;
+
+/* Shape of the packed cache.  Plain data, passed by const pointer.
+ * Supported: head_dim 128; (r_bits, t_bits) with r + t in {6, 8}, 2 <= r, t <= 5
+ * -- (4,4) and (3,3) are the paper's main settings, the others its bit
+ * allocation ablation (Section 6.1); group_tokens 128; any n_kv_heads >= 1. */
+typedef struct {
+  int32_t head_dim;      /* d */
+  int32_t r_bits;        /* radius bits r */
+  int32_t t_bits;        /* angle bits t */
+  int32_t group_tokens;  /* g: tokens per quantization group = tokens per page */
+  int32_t n_kv_heads;
+} pq_layout;
+
+int pq_version(void);
+const char* pq_strerror(int status);
+/* hipError_t of the last failing HIP call on this host thread (0 if none). */
+int pq_last_hip_error(void);
+
+/* Bytes of one page in each pool; 0 if the layout is not supported. */
+size_t pq_codes_bytes_per_page(const pq_layout* layout);
+size_t pq_params_bytes_per_page(const pq_layout* layout);
+size_t pq_values_bytes_per_page(const pq_layout* layout);
+
+/* Bytes of scratch pq_decode_attention needs for n_seqs sequences of at most
+ * max_seq_len tokens (256-byte aligned device memory); 0 on invalid arguments. */
+size_t pq_decode_workspace_bytes(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
+                                 int32_t max_seq_len);
+
+/*
+ * pq_encode_keys -- prefill-time encoder (Section 3.2: pair, radius, angle,
+ * group-wise radius quantization, bit-pack).
+ *
+ *   keys          device, post-RoPE keys of ONE sequence; element i of KV head h of
+ *                 token n is keys[n * token_stride + h * head_stride + i] (strides in
+ *                 elements; the d elements of a head are contiguous)
+ *   key_dtype     PQ_F16 or PQ_F32
+ *   n_tokens      tokens 0 .. n_tokens-1; group k = tokens [k*g, min((k+1)*g, n_tokens));
+ *                 statistics of a partial last group run over its valid tokens
+ *   page_ids      device int32 [ceil(n_tokens / g)]: destination page of each group
+ *   codes_pool, params_pool   device, written for the named pages only (whole pages:
+ *                 padded slots are zero-filled); n_pool_pages is the pool size in pages
+ *                 and page ids outside [0, n_pool_pages) are skipped (nothing is written)
+ *
+ * n_tokens == 0 is a no-op.  Returns PQ_OK once the kernel is enqueued.
+ */
+int pq_encode_keys(const pq_layout* layout, const void* keys, pq_dtype key_dtype,
+                   int64_t token_stride, int64_t head_stride, int64_t n_tokens,
+                   const int32_t* page_ids, void* codes_pool, void* params_pool,
+                   int64_t n_pool_pages, void* hip_stream);
+
+/*
+ * pq_decode_attention -- one decode step per sequence against the packed cache
+ * (Section 3.3 / Appendix A for the table-lookup query-key product; softmax and
+ * fp16 value aggregation are standard attention, Section 2).
+ *
+ *   q             device [n_seqs][n_q_heads][d], post-RoPE, q_dtype PQ_F16 or PQ_F32.
+ *                 Query head h reads KV head h / (n_q_heads / n_kv_heads); the ratio
+ *                 must be 1, 2 or 4
+ *   block_table   device int32 [n_seqs][max_pages_per_seq]: page of tokens
+ *                 [i*g, (i+1)*g) of each sequence; entries past a sequence's last page
+ *                 are ignored
+ *   seq_lens      device int32 [n_seqs]; a length <= 0 gives an all-zero output row;
+ *                 lengths above max_seq_len are treated as max_seq_len
+ *   max_seq_len   host-known upper bound of seq_lens (sizes the launch);
+ *                 ceil(max_seq_len / g) <= max_pages_per_seq
+ *   n_pool_pages  pool size in pages; a block-table entry outside [0, n_pool_pages)
+ *                 makes that page count as masked (no read happens)
+ *   sm_scale      softmax scale (1/sqrt(d) for standard attention)
+ *   out           device fp32 [n_seqs][n_q_heads][d]
+ *   scores        optional device fp32 [n_seqs][n_q_heads][scores_stride]: raw q . k~
+ *                 (before sm_scale) of tokens < seq_len; NULL to skip (timed runs)
+ *   workspace     device, >= pq_decode_workspace_bytes(layout, n_seqs, n_q_heads, max_seq_len),
+ *                 256-byte aligned; contents are scratch
+ *
+ * Scores are accumulated in fp32; probabilities and outputs in fp32.
+ */
+int pq_decode_attention(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
+                        int32_t n_q_heads, const void* codes_pool, const void* params_pool,
+                        const void* v_pool, int64_t n_pool_pages, const int32_t* block_table,
+                        int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
+                        float sm_scale, float* out, float* scores, int64_t scores_stride,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The two stages of pq_decode_attention, callable on their own (the benchmark
+ * times them separately).  pq_decode_partials runs the split-sequence kernel:
+ * every (sequence, KV head, chunk of pages) work-group writes its softmax
+ * partial (running maximum, denominator, un-normalised output) into the
+ * workspace.  pq_decode_merge combines the chunks of each (sequence, query
+ * head) into `out`.  Arguments as in pq_decode_attention.
+ */
+int pq_decode_partials(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
+                       int32_t n_q_heads, const void* codes_pool, const void* params_pool,
+                       const void* v_pool, int64_t n_pool_pages, const int32_t* block_table,
+                       int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
+                       float sm_scale, float* scores, int64_t scores_stride, void* workspace,
+                       size_t workspace_bytes, void* hip_stream);
+int pq_decode_merge(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
+                    const int32_t* seq_lens, int32_t max_seq_len, float* out,
+                    const void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * pq_probe_read_stream -- measurement aid, not part of the method: a plain
+ * 128-bit-load streaming read of `bytes` (multiple of 16) device bytes that
+ * XOR-folds them into sink[0..63] (device uint32[64], so the loads cannot be
+ * elided).  Timed by the benchmark to report what this device streams from HBM.
+ */
+int pq_probe_read_stream(const void* src, size_t bytes, uint32_t* sink, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POLARQUANT_H */

@@ -1,0 +1,104 @@
+// Host-side helpers of libpolarquant: status strings, page sizes, the chunk
+// plan of the split-sequence decode, and the read-stream probe kernel.
+#include <hip/hip_runtime.h>
+
+#include "pq_internal.hpp"
+
+namespace pq {
+
+namespace {
+thread_local int g_last_hip_error = 0;
+}
+
+int record_hip_error(hipError_t e) {
+  g_last_hip_error = static_cast<int>(e);
+  return PQ_ERR_HIP;
+}
+
+bool layout_supported(const pq_layout* l) {
+  if (!l) return false;
+  if (l->head_dim != kHeadDim || l->group_tokens != kGroup || l->n_kv_heads < 1) return false;
+  const int r = l->r_bits, t = l->t_bits, w = r + t;
+  if (r < 2 || r > 5 || t < 2 || t > 5) return false;
+  return w == 6 || w == 8;
+}
+
+// One work-group per (sequence, KV head, chunk).  Chunks are whole pages, a
+// multiple of the 4 wavefronts of a work-group; they shrink until the launch
+// has enough work-groups to fill 256 compute units a few times over.
+ChunkPlan plan_chunks(int32_t n_seqs, int32_t n_kv_heads, int32_t max_seq_len) {
+  const int64_t max_pages = (static_cast<int64_t>(max_seq_len) + kGroup - 1) / kGroup;
+  const int64_t units = static_cast<int64_t>(n_seqs) * n_kv_heads;
+  constexpr int64_t kWantGroups = 2048;
+  int32_t ppc = 32;
+  while (ppc > 4 && units * ((max_pages + ppc - 1) / ppc) < kWantGroups) ppc >>= 1;
+  ChunkPlan p;
+  p.pages_per_chunk = ppc;
+  p.n_chunks = static_cast<int32_t>((max_pages + ppc - 1) / ppc);
+  return p;
+}
+
+namespace {
+
+// Each thread XOR-folds a grid-strided sequence of 16-byte words; one word per
+// work-group slot is written so the loads stay live.
+__global__ __launch_bounds__(256) void pq_read_stream_kernel(const uint4* __restrict__ src, size_t n16,
+                                                            uint32_t* __restrict__ sink) {
+  const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+  size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  uint32_t acc = 0;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  }
+  for (; i < n16; i += stride) {
+    const uint4 a = src[i];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w;
+  }
+  if (acc == 0x9e3779b9u) sink[threadIdx.x & 63] = acc;   // practically never true; keeps the loads
+}
+
+}  // namespace
+}  // namespace pq
+
+using namespace pq;
+
+extern "C" int pq_version(void) { return 100; }
+
+extern "C" const char* pq_strerror(int status) {
+  switch (status) {
+    case PQ_OK: return "ok";
+    case PQ_ERR_INVALID_ARG: return "invalid argument";
+    case PQ_ERR_UNSUPPORTED: return "layout or shape not supported by this build";
+    case PQ_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case PQ_ERR_HIP: return "a HIP call failed (see pq_last_hip_error)";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int pq_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" size_t pq_codes_bytes_per_page(const pq_layout* l) {
+  if (!layout_supported(l)) return 0;
+  return static_cast<size_t>(l->n_kv_heads) * kGroup * kPairs * (l->r_bits + l->t_bits) / 8;
+}
+
+extern "C" size_t pq_params_bytes_per_page(const pq_layout* l) {
+  if (!layout_supported(l)) return 0;
+  return static_cast<size_t>(l->n_kv_heads) * kPairs * 4;
+}
+
+extern "C" size_t pq_values_bytes_per_page(const pq_layout* l) {
+  if (!layout_supported(l)) return 0;
+  return static_cast<size_t>(l->n_kv_heads) * kGroup * kHeadDim * 2;
+}
+
+extern "C" int pq_probe_read_stream(const void* src, size_t bytes, uint32_t* sink, void* hip_stream) {
+  if (!src || !sink || bytes == 0 || (bytes & 15u) || (reinterpret_cast<uintptr_t>(src) & 15u))
+    return PQ_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(pq_read_stream_kernel, dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<const uint4*>(src), bytes / 16, sink);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return record_hip_error(e);
+  return PQ_OK;
+}

@@ -1,0 +1,586 @@
+// Decode attention over the polar-quantized key cache (gfx950).
+//
+// What is computed (paper Section 3.3 and Appendix A): for every query head a
+// table T[j][a] = q_x[j] cos(theta~_a) + q_y[j] sin(theta~_a) over the 2^t angle
+// states is built once; the score of a cached token is
+//     sum_j rho~_j * T[j][a_j],   rho~_j = (c_j + 1/2) s_j + z_j   (Section 3.2),
+// i.e. the dequantize-then-dot product with the multiplications by the query
+// pulled out of the token loop.  Softmax and the fp16 value aggregation that
+// consume the scores are fused behind it (standard attention, Section 2).
+//
+// Mapping to the machine.  One work-group = 4 wavefronts = one (sequence, KV
+// head, chunk of pages); the table of all query heads that share the KV head
+// lives in LDS with the heads interleaved (one 16-byte entry serves 4 heads).
+// Each wavefront owns whole pages (= quantization groups), so a page's radius
+// parameters are loaded once into registers and no work-group barrier is
+// needed inside the loop:
+//   score  : lane = (pair block q = lane / 16, token tk = lane % 16).  One
+//            128-bit (96-bit for w = 6) load brings the 16 symbols of pairs
+//            16q .. 16q+15; the 16 lanes of a row read 16 consecutive units.
+//            The four rows' partial sums are folded with v_permlane32_swap /
+//            v_permlane16_swap so that row h ends up holding head h's score.
+//   softmax: online, per page, in the log2 domain (running max m, sum l).
+//   values : lane = (token slot lane / 16, dims 8*(lane % 16) ..+7); 128-bit
+//            loads of fp16 rows, probabilities broadcast from LDS.
+// A last step folds the four wavefronts' (m, l, acc) into one partial per
+// (sequence, query head, chunk); pq_decode_merge_kernel combines the chunks.
+// No MFMA: the hot loop is a gather-accumulate.
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <math.h>
+
+#include "pq_internal.hpp"
+
+namespace pq {
+
+namespace {
+
+constexpr int kWaves = 4;
+constexpr int kThreads = kWaves * 64;
+constexpr float kNegInf = -INFINITY;
+
+struct DecodeArgs {
+  const void* q;
+  const uint8_t* codes;
+  const uint32_t* params;   // {fp16 s, fp16 z} per pair, viewed as one dword
+  const __half* values;
+  const int32_t* block_table;
+  const int32_t* seq_lens;
+  float* scores;
+  float* ws_acc;            // [seq][q_head][chunk][128]
+  float* ws_ml;             // [seq][q_head][chunk][2] = (m in log2 units, l)
+  int64_t scores_stride;
+  int64_t n_pool_pages;
+  int32_t n_kv_heads;
+  int32_t n_q_heads;
+  int32_t max_pages_per_seq;
+  int32_t max_seq_len;
+  int32_t pages_per_chunk;
+  int32_t n_chunks;
+  float scale_log2;         // sm_scale * log2(e)
+  float cos_tab[kMaxAngleBins];
+  float sin_tab[kMaxAngleBins];
+};
+
+__device__ __forceinline__ uint32_t f2u(float x) { return __float_as_uint(x); }
+__device__ __forceinline__ float u2f(uint32_t x) { return __uint_as_float(x); }
+
+// lanes < 32 get a[l] + a[l+32]; lanes >= 32 get b[l-32] + b[l]
+__device__ __forceinline__ float tsum32(float a, float b) {
+  auto r = __builtin_amdgcn_permlane32_swap(f2u(a), f2u(b), false, false);
+  return u2f(r[0]) + u2f(r[1]);
+}
+// even 16-lane rows get a[row] + a[row+1]; odd rows get b[row-1] + b[row]
+__device__ __forceinline__ float tsum16(float a, float b) {
+  auto r = __builtin_amdgcn_permlane16_swap(f2u(a), f2u(b), false, false);
+  return u2f(r[0]) + u2f(r[1]);
+}
+__device__ __forceinline__ float sum_rows(float x) {   // sum over the 4 rows, result in all rows
+  x = tsum32(x, x);
+  return tsum16(x, x);
+}
+__device__ __forceinline__ float row_max(float x) {    // over the 16 lanes of a row
+  x = fmaxf(x, __shfl_xor(x, 8));
+  x = fmaxf(x, __shfl_xor(x, 4));
+  x = fmaxf(x, __shfl_xor(x, 2));
+  return fmaxf(x, __shfl_xor(x, 1));
+}
+__device__ __forceinline__ float row_sum(float x) {
+  x += __shfl_xor(x, 8);
+  x += __shfl_xor(x, 4);
+  x += __shfl_xor(x, 2);
+  return x + __shfl_xor(x, 1);
+}
+// LDS written by some lanes of this wavefront is about to be read by others.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int NW>
+struct Unit {
+  uint32_t d[NW];
+};
+
+template <int W>
+__device__ __forceinline__ Unit<W / 2> load_unit(const uint8_t* p) {
+  Unit<W / 2> u;
+  if constexpr (W == 8) {
+    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    u.d[0] = v.x; u.d[1] = v.y; u.d[2] = v.z; u.d[3] = v.w;
+  } else {
+    static_assert(W == 6, "unit width");
+    const uint32_t* w = reinterpret_cast<const uint32_t*>(p);
+    u.d[0] = w[0]; u.d[1] = w[1]; u.d[2] = w[2];
+  }
+  return u;
+}
+
+template <int W, int K>
+__device__ __forceinline__ uint32_t symbol(const Unit<W / 2>& u) {
+  constexpr int bit = K * W, wi = bit >> 5, sh = bit & 31;
+  uint32_t v = u.d[wi] >> sh;
+  if constexpr (sh + W > 32) v |= u.d[wi + 1] << (32 - sh);
+  return v & ((1u << W) - 1u);
+}
+
+template <int G>
+struct Heads {
+  float v[G];
+};
+
+template <int G>
+__device__ __forceinline__ Heads<G> lut_read(const uint8_t* p) {
+  Heads<G> t;
+  if constexpr (G == 4) {
+    const float4 f = *reinterpret_cast<const float4*>(p);
+    t.v[0] = f.x; t.v[1] = f.y; t.v[2] = f.z; t.v[3] = f.w;
+  } else if constexpr (G == 2) {
+    const float2 f = *reinterpret_cast<const float2*>(p);
+    t.v[0] = f.x; t.v[1] = f.y;
+  } else {
+    t.v[0] = *reinterpret_cast<const float*>(p);
+  }
+  return t;
+}
+
+template <int G, int RB, int TB, int K>
+__device__ __forceinline__ void score_steps(const Unit<(RB + TB) / 2>& u, const uint8_t* lut_row0,
+                                            const float (&sf)[16], const float (&zz)[16],
+                                            float (&acc)[G]) {
+  if constexpr (K < 16) {
+    constexpr int W = RB + TB;
+    const uint32_t sym = symbol<W, K>(u);
+    const float c = static_cast<float>(sym & ((1u << RB) - 1u));
+    const float rho = fmaf(c, sf[K], zz[K]);
+    const uint32_t a_off = (sym >> RB) << 4;                       // 16-byte table entries
+    const Heads<G> t = lut_read<G>(lut_row0 + K * (16 << TB) + a_off);
+#pragma unroll
+    for (int h = 0; h < G; ++h) acc[h] = fmaf(rho, t.v[h], acc[h]);
+    score_steps<G, RB, TB, K + 1>(u, lut_row0, sf, zz, acc);
+  }
+}
+
+// acc[h][0..7] += sum over the page's tokens (4*it + row) of p_h[token] * V[token][8 dims].
+// vb points at this lane's 8 dims of the page's first value row; pw is prob[token][G].
+template <int G, bool FULL>
+__device__ __forceinline__ void accumulate_values(const __half* vb, const float* pw, int row, int nv,
+                                                  float (&acc)[G][8]) {
+#pragma unroll 2
+  for (int it0 = 0; it0 < 32; it0 += 8) {
+    uint4 vv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int tok = (it0 + i) * 4 + row;
+      if constexpr (FULL) {
+        vv[i] = *reinterpret_cast<const uint4*>(vb + tok * kHeadDim);
+      } else {
+        vv[i] = make_uint4(0u, 0u, 0u, 0u);      // value rows past the sequence end are never read
+        if (tok < nv) vv[i] = *reinterpret_cast<const uint4*>(vb + tok * kHeadDim);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int tok = (it0 + i) * 4 + row;
+      const Heads<G> p = lut_read<G>(reinterpret_cast<const uint8_t*>(pw + tok * G));
+      const uint32_t w4[4] = {vv[i].x, vv[i].y, vv[i].z, vv[i].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const __half2 hv = *reinterpret_cast<const __half2*>(&w4[e]);
+        const float v0 = __low2float(hv), v1 = __high2float(hv);
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          acc[h][2 * e] = fmaf(p.v[h], v0, acc[h][2 * e]);
+          acc[h][2 * e + 1] = fmaf(p.v[h], v1, acc[h][2 * e + 1]);
+        }
+      }
+    }
+  }
+}
+
+template <int G, int RB, int TB, typename QT, bool SCORES>
+__global__ __launch_bounds__(kThreads) void pq_decode_partials_kernel(const DecodeArgs a) {
+  constexpr int W = RB + TB;
+  constexpr int UB = 2 * W;              // bytes per unit
+  constexpr int NA = 1 << TB;            // angle states
+  constexpr int ROW = NA * 16;           // table bytes per pair
+
+  __shared__ __attribute__((aligned(16))) uint8_t lut[kPairs * ROW];
+  __shared__ __attribute__((aligned(16))) float prob[kWaves][kGroup * G];
+  __shared__ __attribute__((aligned(16))) float alpha_s[kWaves][4];
+  __shared__ __attribute__((aligned(16))) float red_acc[kWaves][G][kHeadDim];
+  __shared__ float red_ml[kWaves][G][2];
+
+  const int chunk = blockIdx.x, kvh = blockIdx.y, seq = blockIdx.z;
+  const int L = min(a.seq_lens[seq], a.max_seq_len);
+  if (L <= 0) return;
+  const int n_pages = (L + kGroup - 1) / kGroup;
+  const int page0 = chunk * a.pages_per_chunk;
+  if (page0 >= n_pages) return;
+  const int npg = min(a.pages_per_chunk, n_pages - page0);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  // ---- table of the G query heads that share this KV head (Section 3.3) ----
+  {
+    const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * G) * kHeadDim;
+    float* lf = reinterpret_cast<float*>(lut);
+    for (int idx = tid; idx < kPairs * NA; idx += kThreads) {
+      const int j = idx >> TB, s = idx & (NA - 1);
+      const float cs = a.cos_tab[s], sn = a.sin_tab[s];
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const float qx = static_cast<float>(qb[h * kHeadDim + j]);
+        const float qy = static_cast<float>(qb[h * kHeadDim + j + kPairs]);
+        lf[idx * 4 + h] = fmaf(qx, cs, qy * sn);
+      }
+    }
+  }
+  __syncthreads();
+
+  const int row = lane >> 4;             // score phase: pair block; value phase: token slot
+  const int col = lane & 15;             // score phase: token in the pass; value phase: dim slice
+  const int my_head = (G == 4) ? row : (G == 2 ? (row >> 1) : 0);
+  const bool owner = (G == 4) || (G == 2 && (row & 1) == 0) || (G == 1 && row == 0);
+
+  float m_run = kNegInf, l_run = 0.f;
+  float acc[G][8];
+#pragma unroll
+  for (int h = 0; h < G; ++h)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
+
+  float* const pw = prob[wave];
+  const uint8_t* const lut_row0 = lut + row * (kPairsPerUnit * ROW);
+
+  for (int pg = wave; pg < npg; pg += kWaves) {
+    const int pi = page0 + pg;
+    const int64_t page = a.block_table[static_cast<int64_t>(seq) * a.max_pages_per_seq + pi];
+    if (page < 0 || page >= a.n_pool_pages) continue;              // wave-uniform
+    const int nv = min(kGroup, L - pi * kGroup);
+    const int64_t ph = page * a.n_kv_heads + kvh;
+
+    // radius parameters of this lane's 16 pairs: rho~ = c * s + (z + s/2)
+    float sf[16], zz[16];
+    {
+      const uint4* pp = reinterpret_cast<const uint4*>(a.params + ph * kPairs + row * kPairsPerUnit);
+#pragma unroll
+      for (int v4 = 0; v4 < 4; ++v4) {
+        const uint4 r = pp[v4];
+        const uint32_t w4[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const __half2 sz = *reinterpret_cast<const __half2*>(&w4[e]);
+          const float s = __low2float(sz), z = __high2float(sz);
+          sf[v4 * 4 + e] = s;
+          zz[v4 * 4 + e] = fmaf(0.5f, s, z);
+        }
+      }
+    }
+
+    // ---- scores of the page's 128 tokens: 8 passes of 16 tokens ----
+    const uint8_t* ub = a.codes + ((ph * kBlocks + row) * kGroup + col) * UB;
+    float sc[8];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      Unit<W / 2> u[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) u[i] = load_unit<W>(ub + (half * 4 + i) * 16 * UB);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float part[G];
+#pragma unroll
+        for (int h = 0; h < G; ++h) part[h] = 0.f;
+        score_steps<G, RB, TB, 0>(u[i], lut_row0, sf, zz, part);
+        float s;
+        if constexpr (G == 4) {
+          s = tsum16(tsum32(part[0], part[2]), tsum32(part[1], part[3]));
+        } else if constexpr (G == 2) {
+          const float b = tsum32(part[0], part[1]);
+          s = tsum16(b, b);
+        } else {
+          s = sum_rows(part[0]);
+        }
+        sc[half * 4 + i] = s;
+      }
+    }
+
+    // ---- online softmax over the page (log2 domain) ----
+    float pm = kNegInf;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int tok = i * 16 + col;
+      if constexpr (SCORES) {
+        if (owner && tok < nv)
+          a.scores[(static_cast<int64_t>(seq) * a.n_q_heads + kvh * G + my_head) * a.scores_stride +
+                   static_cast<int64_t>(pi) * kGroup + tok] = sc[i];
+      }
+      sc[i] = (tok < nv) ? sc[i] * a.scale_log2 : kNegInf;
+      pm = fmaxf(pm, sc[i]);
+    }
+    pm = row_max(pm);
+    const float m_new = fmaxf(m_run, pm);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);     // 0 on the first page
+    float psum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float p = __builtin_amdgcn_exp2f(sc[i] - m_new);
+      psum += p;
+      if (owner) pw[(i * 16 + col) * G + my_head] = p;
+    }
+    l_run = fmaf(l_run, alpha, psum);
+    m_run = m_new;
+    if (owner && col == 0) alpha_s[wave][my_head] = alpha;
+    wave_lds_sync();
+
+    // ---- values: acc[h][:] = acc[h][:] * alpha_h + sum_n p_h[n] V[n][:] ----
+    {
+      const float4 al4 = *reinterpret_cast<const float4*>(alpha_s[wave]);
+      const float al[4] = {al4.x, al4.y, al4.z, al4.w};
+#pragma unroll
+      for (int h = 0; h < G; ++h)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[h][e] *= al[h];
+    }
+    const __half* vb = a.values + (ph * kGroup) * kHeadDim + col * 8;
+    if (nv == kGroup) accumulate_values<G, true>(vb, pw, row, nv, acc);
+    else              accumulate_values<G, false>(vb, pw, row, nv, acc);
+    wave_lds_sync();   // the next page overwrites prob[] / alpha_s[]
+  }
+
+  // ---- fold the four wavefronts into one partial per query head ----
+  {
+    const float l_tot = row_sum(l_run);
+    if (owner && col == 0) {
+      red_ml[wave][my_head][0] = m_run;
+      red_ml[wave][my_head][1] = l_tot;
+    }
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      float t[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) t[e] = sum_rows(acc[h][e]);
+      if (row == 0) {
+        float4* dst = reinterpret_cast<float4*>(&red_acc[wave][h][col * 8]);
+        dst[0] = make_float4(t[0], t[1], t[2], t[3]);
+        dst[1] = make_float4(t[4], t[5], t[6], t[7]);
+      }
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * kHeadDim; idx += kThreads) {
+    const int h = idx >> 7, dim = idx & (kHeadDim - 1);
+    float M = kNegInf;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) M = fmaxf(M, red_ml[w][h][0]);
+    float o = 0.f, l = 0.f;
+    if (M > kNegInf) {
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const float wgt = __builtin_amdgcn_exp2f(red_ml[w][h][0] - M);
+        o = fmaf(wgt, red_acc[w][h][dim], o);
+        l = fmaf(wgt, red_ml[w][h][1], l);
+      }
+    }
+    const int64_t slot = (static_cast<int64_t>(seq) * a.n_q_heads + kvh * G + h) * a.n_chunks + chunk;
+    a.ws_acc[slot * kHeadDim + dim] = o;
+    if (dim == 0) {
+      a.ws_ml[slot * 2] = M;
+      a.ws_ml[slot * 2 + 1] = l;
+    }
+  }
+}
+
+// out[seq][head][:] = sum_c 2^(m_c - M) acc_c / sum_c 2^(m_c - M) l_c over the
+// chunks the sequence really has; one work-group of 128 threads per (head, seq).
+__global__ __launch_bounds__(kHeadDim) void pq_decode_merge_kernel(
+    const float* __restrict__ ws_acc, const float* __restrict__ ws_ml,
+    const int32_t* __restrict__ seq_lens, float* __restrict__ out, int32_t n_q_heads,
+    int32_t max_seq_len, int32_t pages_per_chunk, int32_t n_chunks) {
+  const int head = blockIdx.x, seq = blockIdx.y, dim = threadIdx.x;
+  const int L = min(seq_lens[seq], max_seq_len);
+  const int64_t oh = static_cast<int64_t>(seq) * n_q_heads + head;
+  if (L <= 0) {
+    out[oh * kHeadDim + dim] = 0.f;
+    return;
+  }
+  const int n_pages = (L + kGroup - 1) / kGroup;
+  const int nc = (n_pages + pages_per_chunk - 1) / pages_per_chunk;
+  const float* ml = ws_ml + oh * n_chunks * 2;
+  const float* ac = ws_acc + oh * n_chunks * kHeadDim + dim;
+  float M = kNegInf;
+  for (int c = 0; c < nc; ++c) M = fmaxf(M, ml[2 * c]);
+  float o = 0.f, l = 0.f;
+  if (M > kNegInf) {
+    for (int c = 0; c < nc; ++c) {
+      const float w = __builtin_amdgcn_exp2f(ml[2 * c] - M);
+      o = fmaf(w, ac[static_cast<int64_t>(c) * kHeadDim], o);
+      l = fmaf(w, ml[2 * c + 1], l);
+    }
+  }
+  out[oh * kHeadDim + dim] = (l > 0.f) ? o / l : 0.f;
+}
+
+struct Workspace {
+  float* acc;
+  float* ml;
+  size_t bytes;
+};
+
+Workspace carve_workspace(void* base, int32_t n_seqs, int32_t n_q_heads, int32_t n_chunks) {
+  const size_t slots = static_cast<size_t>(n_seqs) * n_q_heads * n_chunks;
+  const size_t acc_bytes = (slots * kHeadDim * sizeof(float) + 255) & ~static_cast<size_t>(255);
+  const size_t ml_bytes = (slots * 2 * sizeof(float) + 255) & ~static_cast<size_t>(255);
+  Workspace w;
+  w.acc = static_cast<float*>(base);
+  w.ml = reinterpret_cast<float*>(static_cast<uint8_t*>(base) + acc_bytes);
+  w.bytes = acc_bytes + ml_bytes;
+  return w;
+}
+
+template <int G, int RB, int TB>
+hipError_t launch_partials(const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st) {
+  const bool sc = a.scores != nullptr;
+  if (qdt == PQ_F16) {
+    if (sc) hipLaunchKernelGGL((pq_decode_partials_kernel<G, RB, TB, __half, true>), grid, dim3(kThreads), 0, st, a);
+    else    hipLaunchKernelGGL((pq_decode_partials_kernel<G, RB, TB, __half, false>), grid, dim3(kThreads), 0, st, a);
+  } else {
+    if (sc) hipLaunchKernelGGL((pq_decode_partials_kernel<G, RB, TB, float, true>), grid, dim3(kThreads), 0, st, a);
+    else    hipLaunchKernelGGL((pq_decode_partials_kernel<G, RB, TB, float, false>), grid, dim3(kThreads), 0, st, a);
+  }
+  return hipGetLastError();
+}
+
+template <int RB, int TB>
+hipError_t launch_partials_g(int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st) {
+  switch (G) {
+    case 1: return launch_partials<1, RB, TB>(a, qdt, grid, st);
+    case 2: return launch_partials<2, RB, TB>(a, qdt, grid, st);
+    default: return launch_partials<4, RB, TB>(a, qdt, grid, st);
+  }
+}
+
+int check_decode_shape(const pq_layout* l, int32_t n_seqs, int32_t n_q_heads, int32_t max_seq_len) {
+  if (!l || n_seqs <= 0 || n_q_heads <= 0 || max_seq_len <= 0) return PQ_ERR_INVALID_ARG;
+  if (l->n_kv_heads <= 0 || n_q_heads % l->n_kv_heads != 0) return PQ_ERR_INVALID_ARG;
+  if (!layout_supported(l)) return PQ_ERR_UNSUPPORTED;
+  const int G = n_q_heads / l->n_kv_heads;
+  if (G != 1 && G != 2 && G != 4) return PQ_ERR_UNSUPPORTED;
+  if (n_seqs > 65535 || l->n_kv_heads > 65535 || n_q_heads > 65535) return PQ_ERR_UNSUPPORTED;
+  return PQ_OK;
+}
+
+}  // namespace
+
+}  // namespace pq
+
+using namespace pq;
+
+extern "C" size_t pq_decode_workspace_bytes(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
+                                            int32_t max_seq_len) {
+  if (check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len) != PQ_OK) return 0;
+  const ChunkPlan plan = plan_chunks(n_seqs, layout->n_kv_heads, max_seq_len);
+  return carve_workspace(nullptr, n_seqs, n_q_heads, plan.n_chunks).bytes;
+}
+
+extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
+                                  int32_t n_q_heads, const void* codes_pool, const void* params_pool,
+                                  const void* v_pool, int64_t n_pool_pages, const int32_t* block_table,
+                                  int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
+                                  float sm_scale, float* scores, int64_t scores_stride, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
+  const int st = check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len);
+  if (st != PQ_OK) return st;
+  if (!q || !codes_pool || !params_pool || !v_pool || !block_table || !seq_lens) return PQ_ERR_INVALID_ARG;
+  if (q_dtype != PQ_F16 && q_dtype != PQ_F32) return PQ_ERR_INVALID_ARG;
+  if (n_pool_pages <= 0 || max_pages_per_seq <= 0) return PQ_ERR_INVALID_ARG;
+  const int64_t need_pages = (static_cast<int64_t>(max_seq_len) + kGroup - 1) / kGroup;
+  if (need_pages > max_pages_per_seq) return PQ_ERR_INVALID_ARG;
+  if (scores && scores_stride < max_seq_len) return PQ_ERR_INVALID_ARG;
+  if (!isfinite(sm_scale)) return PQ_ERR_INVALID_ARG;
+
+  const ChunkPlan plan = plan_chunks(n_seqs, layout->n_kv_heads, max_seq_len);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return PQ_ERR_WORKSPACE;
+  const Workspace ws = carve_workspace(workspace, n_seqs, n_q_heads, plan.n_chunks);
+  if (workspace_bytes < ws.bytes) return PQ_ERR_WORKSPACE;
+
+  DecodeArgs a;
+  a.q = q;
+  a.codes = static_cast<const uint8_t*>(codes_pool);
+  a.params = static_cast<const uint32_t*>(params_pool);
+  a.values = static_cast<const __half*>(v_pool);
+  a.block_table = block_table;
+  a.seq_lens = seq_lens;
+  a.scores = scores;
+  a.ws_acc = ws.acc;
+  a.ws_ml = ws.ml;
+  a.scores_stride = scores_stride;
+  a.n_pool_pages = n_pool_pages;
+  a.n_kv_heads = layout->n_kv_heads;
+  a.n_q_heads = n_q_heads;
+  a.max_pages_per_seq = max_pages_per_seq;
+  a.max_seq_len = max_seq_len;
+  a.pages_per_chunk = plan.pages_per_chunk;
+  a.n_chunks = plan.n_chunks;
+  a.scale_log2 = static_cast<float>(static_cast<double>(sm_scale) * 1.4426950408889634074);
+  const int nb = 1 << layout->t_bits;
+  for (int s = 0; s < kMaxAngleBins; ++s) {
+    // centre of angle bin s of the uniform grid over [-pi, pi)
+    const double th = -M_PI + (s + 0.5) * (2.0 * M_PI / nb);
+    a.cos_tab[s] = s < nb ? static_cast<float>(cos(th)) : 0.f;
+    a.sin_tab[s] = s < nb ? static_cast<float>(sin(th)) : 0.f;
+  }
+
+  const dim3 grid(plan.n_chunks, layout->n_kv_heads, n_seqs);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int G = n_q_heads / layout->n_kv_heads;
+  hipError_t e = hipSuccess;
+  const int rt = layout->r_bits * 10 + layout->t_bits;
+  switch (rt) {
+    case 44: e = launch_partials_g<4, 4>(G, a, q_dtype, grid, stream); break;
+    case 33: e = launch_partials_g<3, 3>(G, a, q_dtype, grid, stream); break;
+    case 53: e = launch_partials_g<5, 3>(G, a, q_dtype, grid, stream); break;
+    case 35: e = launch_partials_g<3, 5>(G, a, q_dtype, grid, stream); break;
+    case 42: e = launch_partials_g<4, 2>(G, a, q_dtype, grid, stream); break;
+    case 24: e = launch_partials_g<2, 4>(G, a, q_dtype, grid, stream); break;
+    default: return PQ_ERR_UNSUPPORTED;
+  }
+  if (e != hipSuccess) return record_hip_error(e);
+  return PQ_OK;
+}
+
+extern "C" int pq_decode_merge(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
+                               const int32_t* seq_lens, int32_t max_seq_len, float* out,
+                               const void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int st = check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len);
+  if (st != PQ_OK) return st;
+  if (!seq_lens || !out) return PQ_ERR_INVALID_ARG;
+  const ChunkPlan plan = plan_chunks(n_seqs, layout->n_kv_heads, max_seq_len);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return PQ_ERR_WORKSPACE;
+  const Workspace ws = carve_workspace(const_cast<void*>(workspace), n_seqs, n_q_heads, plan.n_chunks);
+  if (workspace_bytes < ws.bytes) return PQ_ERR_WORKSPACE;
+  hipLaunchKernelGGL(pq_decode_merge_kernel, dim3(n_q_heads, n_seqs), dim3(kHeadDim), 0,
+                     static_cast<hipStream_t>(hip_stream), ws.acc, ws.ml, seq_lens, out, n_q_heads,
+                     max_seq_len, plan.pages_per_chunk, plan.n_chunks);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return record_hip_error(e);
+  return PQ_OK;
+}
+
+extern "C" int pq_decode_attention(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
+                                   int32_t n_q_heads, const void* codes_pool, const void* params_pool,
+                                   const void* v_pool, int64_t n_pool_pages, const int32_t* block_table,
+                                   int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
+                                   float sm_scale, float* out, float* scores, int64_t scores_stride,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!out) return PQ_ERR_INVALID_ARG;
+  const int st = pq_decode_partials(layout, q, q_dtype, n_seqs, n_q_heads, codes_pool, params_pool, v_pool,
+                                    n_pool_pages, block_table, max_pages_per_seq, seq_lens, max_seq_len,
+                                    sm_scale, scores, scores_stride, workspace, workspace_bytes, hip_stream);
+  if (st != PQ_OK) return st;
+  return pq_decode_merge(layout, n_seqs, n_q_heads, seq_lens, max_seq_len, out, workspace, workspace_bytes,
+                         hip_stream);
+}

@@ -1,0 +1,289 @@
+// Prefill-time encoder of the polar-quantized key cache (gfx950).
+//
+// Per pair (x, y) = (K[j], K[j + d/2]) (Section 3.2; pairing of footnote 2 in
+// Section 3.1):   rho = sqrt(x^2 + y^2),  theta = atan2(y, x),
+//   angle code  a = floor((theta + pi) 2^t / 2 pi)    uniform grid over [-pi, pi)
+//   radius code c = Clamp(floor((rho - z) / s), 0, 2^r - 1)
+// with z = min, s = (max - min) / 2^r of rho over the tokens of the group,
+// both rounded to fp16 and used as rounded.  Codes are integer decisions, so
+// the arithmetic that leads to them is pinned:
+//   * rho, (rho - z) / s: IEEE fp32, one rounding per operation, no fused
+//     multiply-add (this file is compiled with floating-point contraction off).
+//   * the angle bin is decided by the sign of exact-to-1e-16 float64 cross
+//     products against the two neighbouring bin-edge directions, so it equals
+//     the floor of the real-number quotient; a point exactly on an edge (only
+//     possible on an axis or a diagonal) belongs to the upper bin, theta = +pi
+//     is clamped into the last bin, and x = y = 0 goes to bin 2^(t-1).
+//
+// One work-group encodes one page (128 tokens) of one KV head: thread =
+// (pair octet o = tid % 8, token slot tid / 8), four tokens per thread.
+#pragma clang fp contract(off)
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <math.h>
+
+#include "pq_internal.hpp"
+
+namespace pq {
+namespace {
+
+constexpr int kEncThreads = 256;
+constexpr int kItems = 4;   // tokens per thread
+
+struct EncodeArgs {
+  const void* keys;
+  const int32_t* page_ids;
+  uint8_t* codes;
+  uint32_t* params;
+  int64_t token_stride;
+  int64_t head_stride;
+  int64_t n_tokens;
+  int64_t n_pool_pages;
+  int32_t n_kv_heads;
+  float bins_per_radian;                 // 2^t / (2 pi)
+  double edge_cos[kMaxAngleBins + 1];    // direction of bin edge k: angle -pi + k * 2 pi / 2^t
+  double edge_sin[kMaxAngleBins + 1];
+};
+
+__device__ __forceinline__ void load8(const __half* p, float (&v)[8]) {
+  const uint4 r = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const __half2 h = *reinterpret_cast<const __half2*>(&w[e]);
+    v[2 * e] = __low2float(h);
+    v[2 * e + 1] = __high2float(h);
+  }
+}
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+  const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+  v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+
+template <int TB>
+__device__ __forceinline__ uint32_t angle_code(float x, float y, const EncodeArgs& a) {
+  constexpr int NB = 1 << TB;
+  if (x == 0.f && y == 0.f) return NB / 2;
+  // first guess in fp32 (within one bin of the truth) ...
+  int k = static_cast<int>(floorf((atan2f(y, x) + 3.14159265358979f) * a.bins_per_radian));
+  k = max(0, min(NB - 1, k));
+  // ... settled by which side of the neighbouring edges the point lies on
+  const double xd = x, yd = y;
+  const double lo = a.edge_cos[k] * yd - a.edge_sin[k] * xd;          // >= 0: at or past edge k
+  const double hi = a.edge_cos[k + 1] * yd - a.edge_sin[k + 1] * xd;  // >= 0: at or past edge k+1
+  if (lo < 0.0) k -= 1;
+  else if (hi >= 0.0) k += 1;
+  return static_cast<uint32_t>(max(0, min(NB - 1, k)));
+}
+
+template <int RB, int TB, typename KT>
+__global__ __launch_bounds__(kEncThreads) void pq_encode_kernel(const EncodeArgs a) {
+  constexpr int W = RB + TB;
+  constexpr int UB = 2 * W;
+  __shared__ float s_mn[kEncThreads / 64][kPairs];
+  __shared__ float s_mx[kEncThreads / 64][kPairs];
+
+  const int grp = blockIdx.x, kvh = blockIdx.y;
+  const int64_t page = a.page_ids[grp];
+  if (page < 0 || page >= a.n_pool_pages) return;
+  const int64_t tok0 = static_cast<int64_t>(grp) * kGroup;
+  const int nv = static_cast<int>(min<int64_t>(kGroup, a.n_tokens - tok0));
+
+  const int tid = threadIdx.x;
+  const int o = tid & 7;          // pairs 8o .. 8o+7
+  const int slot = tid >> 3;      // tokens slot, slot+32, slot+64, slot+96
+  const int wave = tid >> 6;
+
+  float rho[kItems][8];
+  uint32_t ang[kItems][2];        // 8 angle codes, one byte each
+  float mn[8], mx[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { mn[e] = INFINITY; mx[e] = -INFINITY; }
+
+  const KT* base = static_cast<const KT*>(a.keys) + kvh * a.head_stride + o * 8;
+#pragma unroll
+  for (int it = 0; it < kItems; ++it) {
+    const int tok = slot + 32 * it;
+    ang[it][0] = ang[it][1] = 0u;
+    if (tok < nv) {
+      float x[8], y[8];
+      const KT* p = base + (tok0 + tok) * a.token_stride;
+      load8(p, x);
+      load8(p + kPairs, y);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float xx = x[e] * x[e];
+        const float yy = y[e] * y[e];
+        const float r = __fsqrt_rn(xx + yy);
+        rho[it][e] = r;
+        mn[e] = fminf(mn[e], r);
+        mx[e] = fmaxf(mx[e], r);
+        ang[it][e >> 2] |= angle_code<TB>(x[e], y[e], a) << (8 * (e & 3));
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) rho[it][e] = 0.f;
+    }
+  }
+
+  // group statistics: over the 8 token slots of this wavefront, then over the 4 wavefronts
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+#pragma unroll
+    for (int m = 8; m < 64; m <<= 1) {
+      mn[e] = fminf(mn[e], __shfl_xor(mn[e], m));
+      mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], m));
+    }
+  }
+  if ((tid & 63) < 8) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      s_mn[wave][o * 8 + e] = mn[e];
+      s_mx[wave][o * 8 + e] = mx[e];
+    }
+  }
+  __syncthreads();
+
+  float sf[8], zf[8];
+  uint32_t packed_params[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    float lo = s_mn[0][o * 8 + e], hi = s_mx[0][o * 8 + e];
+#pragma unroll
+    for (int w = 1; w < kEncThreads / 64; ++w) {
+      lo = fminf(lo, s_mn[w][o * 8 + e]);
+      hi = fmaxf(hi, s_mx[w][o * 8 + e]);
+    }
+    const float s32 = (hi - lo) * (1.0f / static_cast<float>(1 << RB));   // exact scaling by 2^-r
+    const __half sh = __float2half_rn(s32), zh = __float2half_rn(lo);      // stored in 16 bits (Appendix B.1)
+    sf[e] = __half2float(sh);
+    zf[e] = __half2float(zh);
+    packed_params[e] = static_cast<uint32_t>(__half_as_ushort(sh)) |
+                       (static_cast<uint32_t>(__half_as_ushort(zh)) << 16);
+  }
+  if (slot == 0) {
+    uint4* dst = reinterpret_cast<uint4*>(a.params + (page * a.n_kv_heads + kvh) * kPairs + o * 8);
+    dst[0] = make_uint4(packed_params[0], packed_params[1], packed_params[2], packed_params[3]);
+    dst[1] = make_uint4(packed_params[4], packed_params[5], packed_params[6], packed_params[7]);
+  }
+
+  // radius codes, symbols, and the bit string of this thread's 8 pairs (8*W bits)
+  uint8_t* const cbase = a.codes + ((page * a.n_kv_heads + kvh) * kBlocks + (o >> 1)) * kGroup * UB;
+#pragma unroll
+  for (int it = 0; it < kItems; ++it) {
+    const int tok = slot + 32 * it;
+    uint64_t bits = 0;
+    if (tok < nv) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float qf = 0.f;
+        if (sf[e] != 0.f) {
+          qf = floorf(__fdiv_rn(rho[it][e] - zf[e], sf[e]));
+          qf = fminf(fmaxf(qf, 0.f), static_cast<float>((1 << RB) - 1));
+        }
+        const uint32_t ac = (ang[it][e >> 2] >> (8 * (e & 3))) & 0xffu;
+        const uint64_t sym = (static_cast<uint64_t>(ac) << RB) | static_cast<uint32_t>(qf);
+        bits |= sym << (e * W);
+      }
+    }
+    // the even lane of each (o, o^1) pair stores the whole 16-pair unit
+    const uint32_t lo32 = static_cast<uint32_t>(bits), hi32 = static_cast<uint32_t>(bits >> 32);
+    const uint32_t plo = __shfl_xor(lo32, 1), phi = __shfl_xor(hi32, 1);
+    if ((o & 1) == 0) {
+      uint8_t* dst = cbase + tok * UB;
+      if constexpr (W == 8) {
+        *reinterpret_cast<uint4*>(dst) = make_uint4(lo32, hi32, plo, phi);
+      } else {
+        static_assert(W == 6, "unit width");
+        uint32_t* d32 = reinterpret_cast<uint32_t*>(dst);
+        d32[0] = lo32;
+        d32[1] = (hi32 & 0xffffu) | (plo << 16);
+        d32[2] = (plo >> 16) | (phi << 16);
+      }
+    }
+  }
+}
+
+template <int RB, int TB>
+hipError_t launch_encode(const EncodeArgs& a, pq_dtype dt, dim3 grid, hipStream_t st) {
+  if (dt == PQ_F16) hipLaunchKernelGGL((pq_encode_kernel<RB, TB, __half>), grid, dim3(kEncThreads), 0, st, a);
+  else              hipLaunchKernelGGL((pq_encode_kernel<RB, TB, float>), grid, dim3(kEncThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+}  // namespace pq
+
+using namespace pq;
+
+extern "C" int pq_encode_keys(const pq_layout* layout, const void* keys, pq_dtype key_dtype,
+                              int64_t token_stride, int64_t head_stride, int64_t n_tokens,
+                              const int32_t* page_ids, void* codes_pool, void* params_pool,
+                              int64_t n_pool_pages, void* hip_stream) {
+  if (!layout) return PQ_ERR_INVALID_ARG;
+  if (!layout_supported(layout)) return PQ_ERR_UNSUPPORTED;
+  if (n_tokens < 0 || n_pool_pages <= 0) return PQ_ERR_INVALID_ARG;
+  if (key_dtype != PQ_F16 && key_dtype != PQ_F32) return PQ_ERR_INVALID_ARG;
+  if (n_tokens == 0) return PQ_OK;
+  if (!keys || !page_ids || !codes_pool || !params_pool) return PQ_ERR_INVALID_ARG;
+  // 128-bit loads: rows of a head must start on 16-byte boundaries
+  const int64_t vec = key_dtype == PQ_F16 ? 8 : 4;
+  if ((reinterpret_cast<uintptr_t>(keys) & 15u) || token_stride % vec || head_stride % vec ||
+      token_stride < kHeadDim || head_stride < 0)
+    return PQ_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(codes_pool) & 15u) || (reinterpret_cast<uintptr_t>(params_pool) & 15u))
+    return PQ_ERR_INVALID_ARG;
+  const int64_t n_groups = (n_tokens + kGroup - 1) / kGroup;
+  if (n_groups > 0x7fffffff || layout->n_kv_heads > 65535) return PQ_ERR_UNSUPPORTED;
+
+  EncodeArgs a;
+  a.keys = keys;
+  a.page_ids = page_ids;
+  a.codes = static_cast<uint8_t*>(codes_pool);
+  a.params = static_cast<uint32_t*>(params_pool);
+  a.token_stride = token_stride;
+  a.head_stride = head_stride;
+  a.n_tokens = n_tokens;
+  a.n_pool_pages = n_pool_pages;
+  a.n_kv_heads = layout->n_kv_heads;
+  const int nb = 1 << layout->t_bits;
+  a.bins_per_radian = static_cast<float>(nb / (2.0 * M_PI));
+  for (int k = 0; k <= kMaxAngleBins; ++k) {
+    double c = 0.0, s = 0.0;
+    if (k <= nb) {
+      const double e = -M_PI + (k % nb) * (2.0 * M_PI / nb);
+      c = cos(e);
+      s = sin(e);
+      // edges on an axis or a diagonal are exact directions, so that a point
+      // exactly on them gives a cross product of exactly zero
+      if (fabs(c) < 1e-12) c = 0.0;
+      if (fabs(s) < 1e-12) s = 0.0;
+      if (c == 0.0) s = s > 0 ? 1.0 : -1.0;
+      if (s == 0.0) c = c > 0 ? 1.0 : -1.0;
+      if (fabs(fabs(c) - fabs(s)) < 1e-12) {
+        const double r = sqrt(0.5);
+        c = c > 0 ? r : -r;
+        s = s > 0 ? r : -r;
+      }
+    }
+    a.edge_cos[k] = c;
+    a.edge_sin[k] = s;
+  }
+
+  const dim3 grid(static_cast<uint32_t>(n_groups), layout->n_kv_heads);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = hipSuccess;
+  switch (layout->r_bits * 10 + layout->t_bits) {
+    case 44: e = launch_encode<4, 4>(a, key_dtype, grid, st); break;
+    case 33: e = launch_encode<3, 3>(a, key_dtype, grid, st); break;
+    case 53: e = launch_encode<5, 3>(a, key_dtype, grid, st); break;
+    case 35: e = launch_encode<3, 5>(a, key_dtype, grid, st); break;
+    case 42: e = launch_encode<4, 2>(a, key_dtype, grid, st); break;
+    case 24: e = launch_encode<2, 4>(a, key_dtype, grid, st); break;
+    default: return PQ_ERR_UNSUPPORTED;
+  }
+  if (e != hipSuccess) return record_hip_error(e);
+  return PQ_OK;
+}

@@ -1,0 +1,82 @@
+"""The C-ABI library loads, exports every symbol the public header declares, and its
+host-side logic (sizes, chunk plan, argument checks) behaves -- no GPU needed: every
+call here returns before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2502_00527_amd as pq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(pq.lib_path()):
+        from paper_2502_00527_amd import build
+        build.build(verbose=False)
+    return pq.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "polarquant.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pq_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert {"pq_encode_keys", "pq_decode_attention"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in polarquant.h but not exported"
+    assert set(names) == set(pq._SIGNATURES), "binding and header disagree on the entry points"
+
+
+def test_page_sizes_and_bit_accounting(lib):
+    lay = pq.Layout(128, 4, 4, 128, 8)
+    assert pq.pq_codes_bytes_per_page(lay) == 8 * 128 * 64          # one byte per pair
+    assert pq.pq_params_bytes_per_page(lay) == 8 * 64 * 4
+    assert pq.pq_values_bytes_per_page(lay) == 8 * 128 * 128 * 2
+    # (r+t)/2 bits per element + 16/g bits of parameters (Appendix B.1, uniform angle grid)
+    bits = 8 * (pq.pq_codes_bytes_per_page(lay) + pq.pq_params_bytes_per_page(lay)) / (8 * 128 * 128)
+    assert bits == 4.125
+    lay33 = pq.Layout(128, 3, 3, 128, 8)
+    assert pq.pq_codes_bytes_per_page(lay33) == 8 * 128 * 48
+    for bad in (pq.Layout(64, 4, 4, 128, 8), pq.Layout(128, 4, 3, 128, 8), pq.Layout(128, 4, 4, 64, 8),
+                pq.Layout(128, 6, 2, 128, 8), pq.Layout(128, 4, 4, 128, 0)):
+        assert pq.pq_codes_bytes_per_page(bad) == 0
+
+
+def test_workspace_size_follows_the_chunk_plan(lib):
+    lay = pq.Layout(128, 4, 4, 128, 8)
+    # 16 seqs x 8 kv heads, 256 pages: chunks of 16 pages -> 16 chunks per sequence
+    n = pq.pq_decode_workspace_bytes(lay, 16, 32, 32768)
+    assert n == 16 * 32 * 16 * 128 * 4 + 16 * 32 * 16 * 2 * 4
+    assert pq.pq_decode_workspace_bytes(lay, 1, 32, 1) > 0
+    assert pq.pq_decode_workspace_bytes(lay, 0, 32, 128) == 0
+    assert pq.pq_decode_workspace_bytes(lay, 1, 12, 128) == 0      # 12 query heads over 8 kv heads
+    assert pq.pq_decode_workspace_bytes(lay, 1, 64, 128) == 0      # group of 8 not built
+
+
+def test_argument_errors_are_reported_before_any_launch(lib):
+    lay = pq.Layout(128, 4, 4, 128, 8)
+    null = ctypes.c_void_p(0)
+    st = lib.pq_encode_keys(ctypes.byref(lay), null, 0, 1024, 128, 10, null, null, null, 4, null)
+    assert st == -1 and pq.pq_strerror(st) == "invalid argument"
+    assert lib.pq_encode_keys(ctypes.byref(lay), null, 0, 1024, 128, 0, null, null, null, 4, null) == 0
+    bad = pq.Layout(128, 7, 1, 128, 8)
+    assert lib.pq_encode_keys(ctypes.byref(bad), null, 0, 1024, 128, 10, null, null, null, 4, null) == -2
+    st = lib.pq_decode_attention(ctypes.byref(lay), null, 0, 1, 32, null, null, null, 4, null, 1, null, 128,
+                                 0.1, null, null, 0, null, 0, null)
+    assert st == -1
+    fake = ctypes.c_void_p(4096)
+    st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 4, fake, 1, fake, 128,
+                                0.1, null, 0, null, 0, null)
+    assert st == -3 and "workspace" in pq.pq_strerror(st)
+    # more pages needed than the block table is wide
+    st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 4, fake, 1, fake, 129,
+                                0.1, null, 0, fake, 1 << 20, null)
+    assert st == -1
+    assert pq.pq_version() >= 100

@@ -1,0 +1,167 @@
+"""Parity of the HIP library (through its C ABI) with the CPU oracle, element by element.
+
+Small cases span several pages, several chunks, ragged tails, every supported bit
+allocation and query-group size; full-size cases run the launch configuration the
+benchmark times and compare sampled sequences.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_00527_amd import workloads as W
+
+from parity import (EDGE_FRACTION, OUT_ABS, SCORE_REL, OracleSeq, compare_encoding, score_errors)
+
+pytestmark = pytest.mark.gpu
+
+WL = W.WORKLOADS
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+SMALL = {
+    # name: (workload, explicit lengths or None)
+    "tiny_full_config": (WL["tiny"], None),                                               # G=1, fp32, 32 pages
+    "mha_two_seqs": (WL["mha"].scaled(n_seqs=2, n_q_heads=4, n_kv_heads=4, max_len=700, min_len=700), None),
+    "gqa_ragged_tail": (WL["gqa"].scaled(n_seqs=2, n_q_heads=8, n_kv_heads=2, max_len=1000, min_len=1000), None),
+    "gqa_many_chunks": (WL["gqa"].scaled(n_seqs=1, n_q_heads=4, n_kv_heads=1, max_len=5000, min_len=5000), None),
+    "long33": (WL["long33"].scaled(n_q_heads=8, n_kv_heads=2, max_len=3001, min_len=3001), None),
+    "ragged_pages": (WL["ragged"].scaled(n_seqs=6, n_q_heads=8, n_kv_heads=2, max_len=2000, min_len=1), None),
+    "group_of_two": (WL["gqa"].scaled(n_seqs=2, n_q_heads=4, n_kv_heads=2, max_len=900, min_len=900), None),
+    "edge_lengths": (WL["gqa"].scaled(n_seqs=5, n_q_heads=4, n_kv_heads=1, max_len=300, min_len=300),
+                     np.array([0, 1, 128, 129, 300], np.int32)),
+    "many_units_big_chunks": (WL["mha"].scaled(n_seqs=64, max_len=200, min_len=200), None),
+    "bits_r5t3": (WL["gqa"].scaled(n_seqs=1, n_q_heads=4, n_kv_heads=1, max_len=777, min_len=777, r_bits=5, t_bits=3), None),
+    "bits_r3t5": (WL["gqa"].scaled(n_seqs=1, n_q_heads=4, n_kv_heads=1, max_len=777, min_len=777, r_bits=3, t_bits=5), None),
+    "bits_r4t2": (WL["gqa"].scaled(n_seqs=1, n_q_heads=2, n_kv_heads=1, max_len=777, min_len=777, r_bits=4, t_bits=2), None),
+    "bits_r2t4": (WL["gqa"].scaled(n_seqs=1, n_q_heads=1, n_kv_heads=1, max_len=777, min_len=777, r_bits=2, t_bits=4), None),
+    "tiny33_fp32": (WL["tiny"].scaled(max_len=1500, min_len=1500, r_bits=3, t_bits=3), None),
+}
+
+
+def _check_workload(name, wl, lens, sample_seqs=None, check_scores=True):
+    from paper_2502_00527_amd.cache import build_device_cache
+
+    _say(f"[parity] {name}: S={wl.n_seqs} Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} L<={wl.max_len} "
+         f"r{wl.r_bits}t{wl.t_bits} {wl.key_dtype}")
+    cache = build_device_cache(wl, lens=lens)
+    S, Hq, d, g = wl.n_seqs, wl.n_q_heads, wl.head_dim, wl.group_tokens
+    out = torch.full((S, Hq, d), float("nan"), dtype=torch.float32, device="cuda:0")
+    scores = None
+    if check_scores:
+        scores = torch.full((S, Hq, cache.max_seq_len), float("nan"), dtype=torch.float32, device="cuda:0")
+    _say(f"[parity] {name}: decode launch")
+    cache.decode(out, scores)
+    torch.cuda.synchronize()
+    out_h = out.cpu().numpy()
+    assert np.all(np.isfinite(out_h)), "non-finite attention output"
+
+    q_h = W.queries(wl)
+    seqs = range(S) if sample_seqs is None else sample_seqs
+    n_codes = n_edge = 0
+    worst_score = worst_out = 0.0
+    for s in seqs:
+        L = int(cache.lens[s])
+        if L <= 0:
+            assert not out_h[s].any(), "empty sequence must give a zero output row"
+            continue
+        n_pages = (L + g - 1) // g
+        ids = torch.from_numpy(cache.table[s, :n_pages].astype(np.int64)).to("cuda:0")
+        ref = OracleSeq(wl, s, L)
+        nc, ne = compare_encoding(ref, cache.codes[ids].cpu().numpy(), cache.params[ids].cpu().numpy())
+        n_codes += nc
+        n_edge += ne
+        ref_scores, ref_out, k_hat = ref.attend(q_h[s], cache.sm_scale)
+        if check_scores:
+            got = scores[s, :, :L].cpu().numpy()
+            err = score_errors(got, ref_scores, q_h[s], k_hat)
+            worst_score = max(worst_score, float(err.max()))
+        worst_out = max(worst_out, float(np.abs(out_h[s] - ref_out).max()))
+    _say(f"[parity] {name}: codes={n_codes} edge_mismatches={n_edge} "
+         f"max_score_err={worst_score:.3e} max_out_err={worst_out:.3e}")
+    assert n_edge <= EDGE_FRACTION * n_codes, "too many angle codes differ on bin edges"
+    assert worst_score <= SCORE_REL
+    assert worst_out <= OUT_ABS
+    return cache
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_small_case(name):
+    wl, lens = SMALL[name]
+    _check_workload(name, wl, lens)
+
+
+def test_decode_on_oracle_packed_bytes():
+    """Decode alone: the cache bytes come from the oracle's encoder and packer."""
+    from paper_2502_00527_amd import Layout, pq_decode_attention, pq_decode_workspace_bytes
+
+    wl = WL["gqa"].scaled(n_seqs=2, n_q_heads=8, n_kv_heads=2, max_len=1300, min_len=1300)
+    lens = W.seq_lengths(wl)
+    table, total = W.page_table(wl, lens)
+    g, H, d = wl.group_tokens, wl.n_kv_heads, wl.head_dim
+    codes = np.zeros((total, H, 4, g, 16), np.uint8)
+    params = np.zeros((total, H, 64, 2), np.float16)
+    values = np.zeros((total, H, g, d), np.float16)
+    refs = []
+    for s in range(wl.n_seqs):
+        L = int(lens[s])
+        ref = OracleSeq(wl, s, L)
+        n_pages = ref.codes.shape[0]
+        ids = table[s, :n_pages]
+        codes[ids], params[ids] = ref.codes, ref.params
+        v = np.zeros((n_pages * g, H, d), np.float16)
+        v[:L] = W.values_for_seq(wl, s, L)
+        values[ids] = v.reshape(n_pages, g, H, d).transpose(0, 2, 1, 3)
+        refs.append(ref)
+    dev = "cuda:0"
+    layout = Layout(d, wl.r_bits, wl.t_bits, g, H)
+    ws = torch.empty(pq_decode_workspace_bytes(layout, wl.n_seqs, wl.n_q_heads, wl.max_len), dtype=torch.uint8, device=dev)
+    out = torch.empty((wl.n_seqs, wl.n_q_heads, d), dtype=torch.float32, device=dev)
+    sc = torch.zeros((wl.n_seqs, wl.n_q_heads, wl.max_len), dtype=torch.float32, device=dev)
+    q_h = W.queries(wl)
+    _say("[parity] decode_on_oracle_packed_bytes: launch")
+    pq_decode_attention(layout, torch.from_numpy(q_h).to(dev), torch.from_numpy(codes).to(dev),
+                        torch.from_numpy(params).to(dev), torch.from_numpy(values).to(dev),
+                        torch.from_numpy(table).to(dev), torch.from_numpy(lens).to(dev), wl.max_len,
+                        1.0 / np.sqrt(d), out, ws, sc)
+    torch.cuda.synchronize()
+    for s, ref in enumerate(refs):
+        ref_scores, ref_out, k_hat = ref.attend(q_h[s], 1.0 / np.sqrt(d))
+        err = score_errors(sc[s, :, : ref.length].cpu().numpy(), ref_scores, q_h[s], k_hat)
+        assert err.max() <= SCORE_REL
+        assert np.abs(out[s].cpu().numpy() - ref_out).max() <= OUT_ABS
+
+
+def test_results_are_deterministic():
+    """Two runs of encode + decode give identical bytes."""
+    from paper_2502_00527_amd.cache import build_device_cache
+
+    wl = WL["gqa"].scaled(n_seqs=2, n_q_heads=8, n_kv_heads=2, max_len=2100, min_len=2100)
+    a = build_device_cache(wl)
+    b = build_device_cache(wl)
+    assert torch.equal(a.codes, b.codes)
+    assert torch.equal(a.params.view(torch.int16), b.params.view(torch.int16))
+    oa, ob = a.decode(), b.decode()
+    torch.cuda.synchronize()
+    assert torch.equal(oa, ob)
+
+
+# ---- full-size launch configurations (what the benchmark times), sampled sequences ----
+
+FULL = {
+    "gqa": [0, 11],          # the headline configuration
+    "mha": [5],
+    "long33": [0],
+    "ragged": [0, 37],
+}
+
+
+@pytest.mark.parametrize("name", list(FULL))
+def test_full_size_sampled(name):
+    wl = WL[name]
+    _check_workload(name + "_full", wl, None, sample_seqs=FULL[name])
