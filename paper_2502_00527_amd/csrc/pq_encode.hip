@@ -116,7 +116,7 @@ __global__ __launch_bounds__(kEncThreads) void pq_encode_kernel(const EncodeArgs
       for (int e = 0; e < 8; ++e) {
         const float xx = x[e] * x[e];
         const float yy = y[e] * y[e];
-        const float r = __fsqrt_rn(xx + yy);
+        const float r = sqrtf(xx + yy);   // correctly rounded (the fast-sqrt intrinsic is not)
         rho[it][e] = r;
         mn[e] = fminf(mn[e], r);
         mx[e] = fmaxf(mx[e], r);
@@ -180,7 +180,7 @@ __global__ __launch_bounds__(kEncThreads) void pq_encode_kernel(const EncodeArgs
       for (int e = 0; e < 8; ++e) {
         float qf = 0.f;
         if (sf[e] != 0.f) {
-          qf = floorf(__fdiv_rn(rho[it][e] - zf[e], sf[e]));
+          qf = floorf((rho[it][e] - zf[e]) / sf[e]);        // IEEE division
           qf = fminf(fmaxf(qf, 0.f), static_cast<float>((1 << RB) - 1));
         }
         const uint32_t ac = (ang[it][e >> 2] >> (8 * (e & 3))) & 0xffu;
