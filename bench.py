@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of decode attention over the polar-quantized key cache on one MI355X.
+
+A step is one pass of the whole decode hot path -- table build, table-lookup
+scoring of every cached key, online softmax, fp16 value aggregation, chunk
+merge -- over one batch of synthetic sequences (one decode step per sequence).
+The cache is encoded beforehand by pq_encode_keys and is resident in HBM when
+the timed region starts.  The metric is keys scored per second (query-head x
+cached-token scores); the roofline object prices the dominant kernel
+(pq_decode_partials) against the 8 TB/s HBM peak using the algorithmic bytes of
+the packed cache: per (KV head, token) 64*w/8 B of codes + 2 B of radius
+parameters + 256 B of fp16 values.
+
+Prints ONE JSON line.  `--gpus` above 1 is refused: this build is single-GPU.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def algorithmic_bytes(wl, lens) -> int:
+    """Bytes the method must move per launch: codes + radius params + fp16 values of every
+    cached (KV head, token)."""
+    w = wl.r_bits + wl.t_bits
+    per_token = (wl.head_dim // 2) * w // 8 + (wl.head_dim // 2) * 4 / wl.group_tokens + wl.head_dim * 2
+    return int(round(float(lens.astype("int64").sum()) * wl.n_kv_heads * per_token))
+
+
+def time_region(fn, n, torch):
+    """Average milliseconds of n back-to-back calls of fn on torch's current stream (HIP events)."""
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(n):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) / n
+
+
+def cpu_baseline(wl, lens, budget_s: float = 20.0):
+    """The oracle's decode (unpack -> dequantize -> dot -> softmax -> P.V, float64) timed on the
+    host for whole sequences of the same workload until about `budget_s` seconds are spent."""
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+
+    from oracle import attention, cache_format, polar
+    from paper_2502_00527_amd import workloads as W
+
+    q = W.queries(wl)
+    g = wl.group_tokens
+    scored = 0
+    spent = 0.0
+    n_done = 0
+    with threadpool_limits(limits=1):
+        for s in range(wl.n_seqs):
+            L = int(lens[s])
+            keys = W.keys_for_seq(wl, s, L)
+            enc = polar.encode_keys(keys, wl.r_bits, wl.t_bits, g)                 # not timed: prefill
+            codes, params = cache_format.pack_sequence(enc["a"], enc["c"], enc["scale"], enc["zero"],
+                                                       wl.r_bits, wl.t_bits, g)
+            n_pages = codes.shape[0]
+            vals = np.zeros((n_pages * g, wl.n_kv_heads, wl.head_dim), np.float16)
+            vals[:L] = W.values_for_seq(wl, s, L)
+            v_pool = np.ascontiguousarray(vals.reshape(n_pages, g, wl.n_kv_heads, wl.head_dim).transpose(0, 2, 1, 3))
+            table = np.arange(n_pages, dtype=np.int32)[None, :]
+            t0 = time.perf_counter()
+            attention.decode_attention(q[s:s + 1], codes, params, v_pool, table, np.array([L]), wl.r_bits,
+                                       wl.t_bits, g, 1.0 / np.sqrt(wl.head_dim))
+            spent += time.perf_counter() - t0
+            scored += L * wl.n_q_heads
+            n_done += 1
+            if spent >= budget_s * 0.5 and spent / n_done * (n_done + 1) > budget_s:
+                break
+    return {"value": scored / spent, "unit": "keys/s", "cores": 1, "kind": "oracle",
+            "sample": f"{n_done} of {wl.n_seqs} sequences of the same workload ({scored} scores, "
+                      f"{spent:.1f} s of NumPy float64 decode on one thread; encode not timed)"}
+
+
+def read_traffic_note(workload: str):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc, if a
+    committed summary states it (profiles/decode_partials_<workload>_pmc.txt)."""
+    path = os.path.join(ROOT, "profiles", f"decode_partials_{workload}_pmc.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return int(float(line.split(":", 1)[1].split()[0]))
+    except OSError:
+        pass
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="gqa", choices=["gqa", "mha", "long33", "ragged", "tiny"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=20.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2502_00527_amd as pq
+    from paper_2502_00527_amd import workloads as W
+    from paper_2502_00527_amd.cache import build_device_cache
+
+    pq.load_library()          # raises if libpolarquant.so is not built: there is no fallback
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    wl = W.WORKLOADS[args.workload]
+    t0 = time.time()
+    cache = build_device_cache(wl, progress=lambda s: print(f"[bench] encoded sequence {s + 1}/{wl.n_seqs}",
+                                                            file=sys.stderr, flush=True))
+    torch.cuda.synchronize()
+    print(f"[bench] inputs ready in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+    lens = cache.lens
+    out = torch.empty((wl.n_seqs, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device="cuda:0")
+
+    def step():
+        cache.decode(out)
+
+    def partials_only():
+        pq.pq_decode_partials(cache.layout, cache.q, cache.codes, cache.params, cache.values, cache.block_table,
+                              cache.seq_lens, cache.max_seq_len, cache.sm_scale, cache.workspace)
+
+    def merge_only():
+        pq.pq_decode_merge(cache.layout, wl.n_seqs, wl.n_q_heads, cache.seq_lens, cache.max_seq_len, out,
+                           cache.workspace)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    ms_step = time_region(step, args.steps, torch)
+    wall = time.perf_counter() - t_start
+    # the dominant kernel alone, same launch configuration, same stream
+    ms_partials = time_region(partials_only, args.steps, torch)
+    ms_merge = time_region(merge_only, args.steps, torch)
+
+    # what this device streams with plain 128-bit loads (context for the roofline fraction)
+    probe = torch.empty(2 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+    sink = torch.zeros(64, dtype=torch.int32, device="cuda:0")
+    for _ in range(3):
+        pq.pq_probe_read_stream(probe, sink)
+    ms_probe = time_region(lambda: pq.pq_probe_read_stream(probe, sink), 20, torch)
+    read_stream_gbps = probe.numel() / (ms_probe * 1e-3) / 1e9
+    del probe
+
+    keys_scored = int(lens.astype(np.int64).sum()) * wl.n_q_heads
+    alg_bytes = algorithmic_bytes(wl, lens)
+    achieved = alg_bytes / (ms_partials * 1e-3) / 1e9
+    result = {
+        "metric": "decode keys scored/sec on polar-quantized cache",
+        "value": keys_scored / (ms_step * 1e-3),
+        "unit": "keys/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.n_seqs} seqs x {wl.n_q_heads} q heads over {wl.n_kv_heads} kv heads, "
+                               f"head_dim {wl.head_dim}, context {wl.min_len}..{wl.max_len}, r{wl.r_bits}/t{wl.t_bits}, "
+                               f"group {wl.group_tokens}, fp16 values, RoPE base {wl.rope_base:g}",
+                   "keys_scored_per_step": keys_scored,
+                   "kv_tokens_per_step": int(lens.astype(np.int64).sum()) * wl.n_kv_heads},
+        "roofline": {"bound": "hbm", "kernel": "pq_decode_partials_kernel", "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": read_traffic_note(wl.name), "algorithmic_bytes": alg_bytes,
+                     "ms_per_launch": ms_partials, "ms_merge_kernel": ms_merge,
+                     "read_stream_GBps": read_stream_gbps,
+                     "frac_of_read_stream": achieved / read_stream_gbps,
+                     "whole_step_GBps": alg_bytes / (ms_step * 1e-3) / 1e9},
+        "wall_s_timed_region": wall,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, lens, args.cpu_budget)
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
