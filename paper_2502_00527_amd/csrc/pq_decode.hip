@@ -98,21 +98,49 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+#ifndef PQ_WAVES_PER_EU
+#define PQ_WAVES_PER_EU 2
+#endif
+#define PQ_KERNEL_ATTR \
+  __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(PQ_WAVES_PER_EU, PQ_WAVES_PER_EU)))
+
+// ---- streaming loads --------------------------------------------------------
+// Codes, parameters and values are read through buffer descriptors that cover
+// exactly one page of one KV head: the lane offset stays in one VGPR, the
+// position inside the page is a scalar/immediate offset, and a read past the
+// descriptor's size returns zeros instead of faulting (value rows beyond the
+// sequence end are masked that way).  Everything streamed is read once, so the
+// loads are non-temporal.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+constexpr int kAuxStream = 2;     // gfx950 cache-policy bit "nt"
+constexpr int kAuxCached = 0;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  // raw buffer, 32-bit data format, no swizzle
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, static_cast<int>(bytes), 0x00020000);
+}
+template <int AUX>
+__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, AUX);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 template <int NW>
 struct Unit {
   uint32_t d[NW];
 };
 
 template <int W>
-__device__ __forceinline__ Unit<W / 2> load_unit(const uint8_t* p) {
+__device__ __forceinline__ Unit<W / 2> load_unit(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
   Unit<W / 2> u;
   if constexpr (W == 8) {
-    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, kAuxStream);
     u.d[0] = v.x; u.d[1] = v.y; u.d[2] = v.z; u.d[3] = v.w;
   } else {
     static_assert(W == 6, "unit width");
-    const uint32_t* w = reinterpret_cast<const uint32_t*>(p);
-    u.d[0] = w[0]; u.d[1] = w[1]; u.d[2] = w[2];
+    const u32x3 v = __builtin_amdgcn_raw_buffer_load_b96(r, voff, soff, kAuxStream);
+    u.d[0] = v.x; u.d[1] = v.y; u.d[2] = v.z;
   }
   return u;
 }
@@ -130,77 +158,111 @@ struct Heads {
   float v[G];
 };
 
+// LDS is addressed by 32-bit byte addresses (address space 3) so that the table
+// gather is a ds_read with an immediate offset.
+#define PQ_LDS __attribute__((address_space(3)))
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((const PQ_LDS uint8_t*)p));
+}
+
 template <int G>
-__device__ __forceinline__ Heads<G> lut_read(const uint8_t* p) {
+__device__ __forceinline__ Heads<G> lut_read(uint32_t addr) {
   Heads<G> t;
   if constexpr (G == 4) {
-    const float4 f = *reinterpret_cast<const float4*>(p);
+    const f32x4 f = *(const PQ_LDS f32x4*)static_cast<uintptr_t>(addr);
     t.v[0] = f.x; t.v[1] = f.y; t.v[2] = f.z; t.v[3] = f.w;
   } else if constexpr (G == 2) {
-    const float2 f = *reinterpret_cast<const float2*>(p);
+    const f32x2 f = *(const PQ_LDS f32x2*)static_cast<uintptr_t>(addr);
     t.v[0] = f.x; t.v[1] = f.y;
   } else {
-    t.v[0] = *reinterpret_cast<const float*>(p);
+    t.v[0] = *(const PQ_LDS float*)static_cast<uintptr_t>(addr);
   }
   return t;
 }
 
+// Byte B of `x` as a float / added to `base`: one instruction each on gfx9
+// (v_cvt_f32_ubyteB, and v_add_u32 with a sub-dword operand select).
+template <int B>
+__device__ __forceinline__ float byte_to_float(uint32_t x) {
+  float f;
+  if constexpr (B == 0) asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(f) : "v"(x));
+  else if constexpr (B == 1) asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(f) : "v"(x));
+  else if constexpr (B == 2) asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(f) : "v"(x));
+  else asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(f) : "v"(x));
+  return f;
+}
+template <int B>
+__device__ __forceinline__ uint32_t add_byte(uint32_t x, uint32_t base) {
+  uint32_t r;
+  if constexpr (B == 0)
+    asm("v_add_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(base));
+  else if constexpr (B == 1)
+    asm("v_add_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(base));
+  else if constexpr (B == 2)
+    asm("v_add_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(base));
+  else
+    asm("v_add_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3 src1_sel:DWORD" : "=v"(r) : "v"(x), "v"(base));
+  return r;
+}
+
+// One pair step: part[h] += rho~ * T[h][pair K of this lane's block][angle code].
+// `lut_row0` is the LDS byte address of the lane's block (pair 16*row); radius
+// parameters are (s, z + s/2) so that rho~ = c * s + zz.
 template <int G, int RB, int TB, int K>
-__device__ __forceinline__ void score_steps(const Unit<(RB + TB) / 2>& u, const uint8_t* lut_row0,
+__device__ __forceinline__ void score_steps(const Unit<(RB + TB) / 2>& u, uint32_t lut_row0,
                                             const float (&sf)[16], const float (&zz)[16],
-                                            float (&acc)[G]) {
+                                            float (&part)[G]) {
   if constexpr (K < 16) {
     constexpr int W = RB + TB;
-    const uint32_t sym = symbol<W, K>(u);
-    const float c = static_cast<float>(sym & ((1u << RB) - 1u));
+    constexpr int ROW = 16 << TB;
+    float c;
+    uint32_t addr;
+    if constexpr (RB == 4 && TB == 4) {
+      // byte K of the unit is (a << 4) | c: mask once per dword, then one op per field
+      const uint32_t d = u.d[K >> 2];
+      const uint32_t rad = d & 0x0f0f0f0fu, ang = d & 0xf0f0f0f0u;   // CSE'd across the dword's 4 pairs
+      c = byte_to_float<K & 3>(rad);
+      addr = add_byte<K & 3>(ang, lut_row0);                        // (a << 4) is the entry's byte offset
+    } else {
+      const uint32_t sym = symbol<W, K>(u);
+      c = static_cast<float>(sym & ((1u << RB) - 1u));
+      addr = lut_row0 + ((sym >> RB) << 4);
+    }
     const float rho = fmaf(c, sf[K], zz[K]);
-    const uint32_t a_off = (sym >> RB) << 4;                       // 16-byte table entries
-    const Heads<G> t = lut_read<G>(lut_row0 + K * (16 << TB) + a_off);
+    const Heads<G> t = lut_read<G>(addr + K * ROW);
 #pragma unroll
-    for (int h = 0; h < G; ++h) acc[h] = fmaf(rho, t.v[h], acc[h]);
-    score_steps<G, RB, TB, K + 1>(u, lut_row0, sf, zz, acc);
+    for (int h = 0; h < G; ++h) part[h] = fmaf(rho, t.v[h], part[h]);
+    score_steps<G, RB, TB, K + 1>(u, lut_row0, sf, zz, part);
   }
 }
 
-// acc[h][0..7] += sum over the page's tokens (4*it + row) of p_h[token] * V[token][8 dims].
-// vb points at this lane's 8 dims of the page's first value row; pw is prob[token][G].
-template <int G, bool FULL>
-__device__ __forceinline__ void accumulate_values(const __half* vb, const float* pw, int row, int nv,
-                                                  float (&acc)[G][8]) {
-#pragma unroll 2
-  for (int it0 = 0; it0 < 32; it0 += 8) {
-    uint4 vv[8];
+// acc[h][0..7] += p_h[token] * V[token][this lane's 8 dims] for the 8 value rows in `vv`
+// (tokens 4 * (it0 + i) + row); pw is prob[token][G] in LDS.
+template <int G>
+__device__ __forceinline__ void consume_values(const uint4 (&vv)[8], int it0, uint32_t pw, int row,
+                                               float (&acc)[G][8]) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int tok = (it0 + i) * 4 + row;
-      if constexpr (FULL) {
-        vv[i] = *reinterpret_cast<const uint4*>(vb + tok * kHeadDim);
-      } else {
-        vv[i] = make_uint4(0u, 0u, 0u, 0u);      // value rows past the sequence end are never read
-        if (tok < nv) vv[i] = *reinterpret_cast<const uint4*>(vb + tok * kHeadDim);
-      }
-    }
+  for (int i = 0; i < 8; ++i) {
+    const int tok = (it0 + i) * 4 + row;
+    const Heads<G> p = lut_read<G>(pw + tok * (G * 4));
+    const uint32_t w4[4] = {vv[i].x, vv[i].y, vv[i].z, vv[i].w};
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int tok = (it0 + i) * 4 + row;
-      const Heads<G> p = lut_read<G>(reinterpret_cast<const uint8_t*>(pw + tok * G));
-      const uint32_t w4[4] = {vv[i].x, vv[i].y, vv[i].z, vv[i].w};
+    for (int e = 0; e < 4; ++e) {
+      const __half2 hv = *reinterpret_cast<const __half2*>(&w4[e]);
+      const float v0 = __low2float(hv), v1 = __high2float(hv);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const __half2 hv = *reinterpret_cast<const __half2*>(&w4[e]);
-        const float v0 = __low2float(hv), v1 = __high2float(hv);
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-          acc[h][2 * e] = fmaf(p.v[h], v0, acc[h][2 * e]);
-          acc[h][2 * e + 1] = fmaf(p.v[h], v1, acc[h][2 * e + 1]);
-        }
+      for (int h = 0; h < G; ++h) {
+        acc[h][2 * e] = fmaf(p.v[h], v0, acc[h][2 * e]);
+        acc[h][2 * e + 1] = fmaf(p.v[h], v1, acc[h][2 * e + 1]);
       }
     }
   }
 }
 
 template <int G, int RB, int TB, typename QT, bool SCORES>
-__global__ __launch_bounds__(kThreads) void pq_decode_partials_kernel(const DecodeArgs a) {
+__global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   constexpr int W = RB + TB;
   constexpr int UB = 2 * W;              // bytes per unit
   constexpr int NA = 1 << TB;            // angle states
@@ -254,7 +316,11 @@ __global__ __launch_bounds__(kThreads) void pq_decode_partials_kernel(const Deco
     for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
 
   float* const pw = prob[wave];
-  const uint8_t* const lut_row0 = lut + row * (kPairsPerUnit * ROW);
+  const uint32_t lut_row0 = lds_addr(lut) + row * (kPairsPerUnit * ROW);
+  const uint32_t pw_addr = lds_addr(pw);
+  const uint32_t voff_codes = (row * kGroup + col) * UB;          // unit of (block row, token col) of pass 0
+  const uint32_t voff_params = row * (kPairsPerUnit * 4);
+  const uint32_t voff_values = row * (kHeadDim * 2) + col * 16;   // token slot row, dims 8*col..
 
   for (int pg = wave; pg < npg; pg += kWaves) {
     const int pi = page0 + pg;
@@ -262,49 +328,53 @@ __global__ __launch_bounds__(kThreads) void pq_decode_partials_kernel(const Deco
     if (page < 0 || page >= a.n_pool_pages) continue;              // wave-uniform
     const int nv = min(kGroup, L - pi * kGroup);
     const int64_t ph = page * a.n_kv_heads + kvh;
+    const __amdgpu_buffer_rsrc_t rs_codes = make_rsrc(a.codes + ph * (kBlocks * kGroup * UB), kBlocks * kGroup * UB);
+    const __amdgpu_buffer_rsrc_t rs_params = make_rsrc(a.params + ph * kPairs, kPairs * 4);
+    const __amdgpu_buffer_rsrc_t rs_values = make_rsrc(a.values + ph * (kGroup * kHeadDim), nv * (kHeadDim * 2));
+
+    // ---- issue the page's loads: parameters, all 8 code units, the first 16 value rows ----
+    uint4 praw[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) praw[i] = buf_load16<kAuxCached>(rs_params, voff_params, i * 16);
+    Unit<W / 2> cu[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) cu[i] = load_unit<W>(rs_codes, voff_codes, i * 16 * UB);
+    uint4 vx[8], vy[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) vx[i] = buf_load16<kAuxStream>(rs_values, voff_values, i * 1024);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) vy[i] = buf_load16<kAuxStream>(rs_values, voff_values, (8 + i) * 1024);
+    __builtin_amdgcn_sched_barrier(0);
 
     // radius parameters of this lane's 16 pairs: rho~ = c * s + (z + s/2)
     float sf[16], zz[16];
-    {
-      const uint4* pp = reinterpret_cast<const uint4*>(a.params + ph * kPairs + row * kPairsPerUnit);
 #pragma unroll
-      for (int v4 = 0; v4 < 4; ++v4) {
-        const uint4 r = pp[v4];
-        const uint32_t w4[4] = {r.x, r.y, r.z, r.w};
+    for (int v4 = 0; v4 < 4; ++v4) {
+      const uint32_t w4[4] = {praw[v4].x, praw[v4].y, praw[v4].z, praw[v4].w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const __half2 sz = *reinterpret_cast<const __half2*>(&w4[e]);
-          const float s = __low2float(sz), z = __high2float(sz);
-          sf[v4 * 4 + e] = s;
-          zz[v4 * 4 + e] = fmaf(0.5f, s, z);
-        }
+      for (int e = 0; e < 4; ++e) {
+        const __half2 sz = *reinterpret_cast<const __half2*>(&w4[e]);
+        const float s = __low2float(sz), z = __high2float(sz);
+        sf[v4 * 4 + e] = s;
+        zz[v4 * 4 + e] = fmaf(0.5f, s, z);
       }
     }
 
     // ---- scores of the page's 128 tokens: 8 passes of 16 tokens ----
-    const uint8_t* ub = a.codes + ((ph * kBlocks + row) * kGroup + col) * UB;
     float sc[8];
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      Unit<W / 2> u[4];
+    for (int i = 0; i < 8; ++i) {
+      float part[G];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) u[i] = load_unit<W>(ub + (half * 4 + i) * 16 * UB);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float part[G];
-#pragma unroll
-        for (int h = 0; h < G; ++h) part[h] = 0.f;
-        score_steps<G, RB, TB, 0>(u[i], lut_row0, sf, zz, part);
-        float s;
-        if constexpr (G == 4) {
-          s = tsum16(tsum32(part[0], part[2]), tsum32(part[1], part[3]));
-        } else if constexpr (G == 2) {
-          const float b = tsum32(part[0], part[1]);
-          s = tsum16(b, b);
-        } else {
-          s = sum_rows(part[0]);
-        }
-        sc[half * 4 + i] = s;
+      for (int h = 0; h < G; ++h) part[h] = 0.f;
+      score_steps<G, RB, TB, 0>(cu[i], lut_row0, sf, zz, part);
+      if constexpr (G == 4) {
+        sc[i] = tsum16(tsum32(part[0], part[2]), tsum32(part[1], part[3]));
+      } else if constexpr (G == 2) {
+        const float b = tsum32(part[0], part[1]);
+        sc[i] = tsum16(b, b);
+      } else {
+        sc[i] = sum_rows(part[0]);
       }
     }
 
@@ -345,9 +415,16 @@ __global__ __launch_bounds__(kThreads) void pq_decode_partials_kernel(const Deco
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[h][e] *= al[h];
     }
-    const __half* vb = a.values + (ph * kGroup) * kHeadDim + col * 8;
-    if (nv == kGroup) accumulate_values<G, true>(vb, pw, row, nv, acc);
-    else              accumulate_values<G, false>(vb, pw, row, nv, acc);
+    consume_values<G>(vx, 0, pw_addr, row, acc);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) vx[i] = buf_load16<kAuxStream>(rs_values, voff_values, (16 + i) * 1024);
+    __builtin_amdgcn_sched_barrier(0);
+    consume_values<G>(vy, 8, pw_addr, row, acc);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) vy[i] = buf_load16<kAuxStream>(rs_values, voff_values, (24 + i) * 1024);
+    __builtin_amdgcn_sched_barrier(0);
+    consume_values<G>(vx, 16, pw_addr, row, acc);
+    consume_values<G>(vy, 24, pw_addr, row, acc);
     wave_lds_sync();   // the next page overwrites prob[] / alpha_s[]
   }
 
