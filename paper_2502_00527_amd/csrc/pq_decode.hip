@@ -29,6 +29,8 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 
+#include <type_traits>
+
 #include "pq_internal.hpp"
 
 namespace pq {
@@ -117,6 +119,9 @@ constexpr int kAuxStream = 2;     // gfx950 cache-policy bit "nt"
 constexpr int kAuxCached = 0;
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+#ifdef PQ_EXP_NOMEM
+  bytes = 0;
+#endif
   // raw buffer, 32-bit data format, no swizzle
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, static_cast<int>(bytes), 0x00020000);
 }
@@ -238,13 +243,13 @@ __device__ __forceinline__ void score_steps(const Unit<(RB + TB) / 2>& u, uint32
   }
 }
 
-// acc[h][0..7] += p_h[token] * V[token][this lane's 8 dims] for the 8 value rows in `vv`
+// acc[h][0..7] += p_h[token] * V[token][this lane's 8 dims] for the 4 value rows in `vv`
 // (tokens 4 * (it0 + i) + row); pw is prob[token][G] in LDS.
 template <int G>
-__device__ __forceinline__ void consume_values(const uint4 (&vv)[8], int it0, uint32_t pw, int row,
+__device__ __forceinline__ void consume_values(const uint4 (&vv)[4], int it0, uint32_t pw, int row,
                                                float (&acc)[G][8]) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
+  for (int i = 0; i < 4; ++i) {
     const int tok = (it0 + i) * 4 + row;
     const Heads<G> p = lut_read<G>(pw + tok * (G * 4));
     const uint32_t w4[4] = {vv[i].x, vv[i].y, vv[i].z, vv[i].w};
@@ -315,36 +320,71 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
 
-  float* const pw = prob[wave];
   const uint32_t lut_row0 = lds_addr(lut) + row * (kPairsPerUnit * ROW);
-  const uint32_t pw_addr = lds_addr(pw);
+  const uint32_t pw_addr = lds_addr(prob[wave]);
   const uint32_t voff_codes = (row * kGroup + col) * UB;          // unit of (block row, token col) of pass 0
   const uint32_t voff_params = row * (kPairsPerUnit * 4);
   const uint32_t voff_values = row * (kHeadDim * 2) + col * 16;   // token slot row, dims 8*col..
 
-  for (int pg = wave; pg < npg; pg += kWaves) {
-    const int pi = page0 + pg;
-    const int64_t page = a.block_table[static_cast<int64_t>(seq) * a.max_pages_per_seq + pi];
-    if (page < 0 || page >= a.n_pool_pages) continue;              // wave-uniform
-    const int nv = min(kGroup, L - pi * kGroup);
-    const int64_t ph = page * a.n_kv_heads + kvh;
-    const __amdgpu_buffer_rsrc_t rs_codes = make_rsrc(a.codes + ph * (kBlocks * kGroup * UB), kBlocks * kGroup * UB);
-    const __amdgpu_buffer_rsrc_t rs_params = make_rsrc(a.params + ph * kPairs, kPairs * 4);
-    const __amdgpu_buffer_rsrc_t rs_values = make_rsrc(a.values + ph * (kGroup * kHeadDim), nv * (kHeadDim * 2));
+  // This wavefront's pages are chunk pages wave, wave + 4, ...; lane k remembers the pool page
+  // of the k-th of them (-1 if the block table entry is out of range: such a page is masked).
+  const int n_w = npg > wave ? (npg - wave + kWaves - 1) / kWaves : 0;
+  int pid_lane = -1;
+  if (lane < n_w) {
+    const int64_t pid = a.block_table[static_cast<int64_t>(seq) * a.max_pages_per_seq + page0 + wave + kWaves * lane];
+    if (pid >= 0 && pid < a.n_pool_pages) pid_lane = static_cast<int>(pid);
+  }
+  constexpr uint32_t kCodesBytes = kBlocks * kGroup * UB;          // codes of one (page, kv head)
+  // Buffer descriptors of the wavefront's k-th page; a masked page gets empty descriptors
+  // (every read returns zero) and zero valid tokens.
+  auto page_setup = [&](int k, __amdgpu_buffer_rsrc_t& rc, __amdgpu_buffer_rsrc_t& rp,
+                        __amdgpu_buffer_rsrc_t& rv, int& nv) {
+    const int pid = __builtin_amdgcn_readlane(pid_lane, k);
+    const bool ok = pid >= 0;
+    const int64_t ph = ok ? static_cast<int64_t>(pid) * a.n_kv_heads + kvh : 0;
+    nv = ok ? min(kGroup, L - (page0 + wave + kWaves * k) * kGroup) : 0;
+    rc = make_rsrc(a.codes + ph * kCodesBytes, ok ? kCodesBytes : 0u);
+    rp = make_rsrc(a.params + ph * kPairs, ok ? kPairs * 4u : 0u);
+    rv = make_rsrc(a.values + ph * (kGroup * kHeadDim), static_cast<uint32_t>(nv) * (kHeadDim * 2));
+  };
 
-    // ---- issue the page's loads: parameters, all 8 code units, the first 16 value rows ----
-    uint4 praw[4];
+  // ---- loop over the wavefront's pages ---------------------------------------------------
+  // Per page: score its 128 tokens (8 passes), online softmax, then aggregate its 32 x 4 value
+  // rows.  Loads run ahead of their use:
+  //   * value rows ride in a ring of 4 x 4 register quads; a quad is refilled, as soon as it has
+  //     been consumed, with the row 16 further on -- the last 16 refills of a page fetch the
+  //     first 16 rows of the NEXT page, which then arrive during that page's score phase;
+  //   * codes and parameters of the next page are loaded at the start of the value phase, into
+  //     registers the score phase has just released.
+  // When there is no next page those loads go to an empty descriptor: they return zeros
+  // without touching memory, so the loop body has no branches.
+  const __amdgpu_buffer_rsrc_t rs_empty = make_rsrc(a.values, 0u);
+  __amdgpu_buffer_rsrc_t rc_cur = rs_empty, rp_cur = rs_empty, rv_cur = rs_empty;
+  __amdgpu_buffer_rsrc_t rc_nxt = rs_empty, rp_nxt = rs_empty, rv_nxt = rs_empty;
+  int nv_cur = 0, nv_nxt = 0;
+  uint4 praw[4];
+  Unit<W / 2> cu[8];
+  uint4 ring[4][4];
+  if (n_w > 0) {
+    page_setup(0, rc_cur, rp_cur, rv_cur, nv_cur);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) praw[i] = buf_load16<kAuxCached>(rs_params, voff_params, i * 16);
-    Unit<W / 2> cu[8];
+    for (int i = 0; i < 4; ++i) praw[i] = buf_load16<kAuxCached>(rp_cur, voff_params, i * 16);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) cu[i] = load_unit<W>(rs_codes, voff_codes, i * 16 * UB);
-    uint4 vx[8], vy[8];
+    for (int i = 0; i < 8; ++i) cu[i] = load_unit<W>(rc_cur, voff_codes, i * 16 * UB);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) vx[i] = buf_load16<kAuxStream>(rs_values, voff_values, i * 1024);
+    for (int k = 0; k < 4; ++k)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) vy[i] = buf_load16<kAuxStream>(rs_values, voff_values, (8 + i) * 1024);
-    __builtin_amdgcn_sched_barrier(0);
+      for (int r = 0; r < 4; ++r) ring[k][r] = buf_load16<kAuxStream>(rv_cur, voff_values, (4 * k + r) * 1024);
+  }
+
+  for (int i = 0; i < n_w; ++i) {
+    const int pi = page0 + wave + kWaves * i;                      // chunk-relative page of iteration i
+    if (i + 1 < n_w) {
+      page_setup(i + 1, rc_nxt, rp_nxt, rv_nxt, nv_nxt);
+    } else {
+      rc_nxt = rp_nxt = rv_nxt = rs_empty;
+      nv_nxt = 0;
+    }
 
     // radius parameters of this lane's 16 pairs: rho~ = c * s + (z + s/2)
     float sf[16], zz[16];
@@ -363,69 +403,88 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
     // ---- scores of the page's 128 tokens: 8 passes of 16 tokens ----
     float sc[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int s = 0; s < 8; ++s) {
       float part[G];
 #pragma unroll
       for (int h = 0; h < G; ++h) part[h] = 0.f;
-      score_steps<G, RB, TB, 0>(cu[i], lut_row0, sf, zz, part);
+#ifdef PQ_EXP_NOCOMPUTE
+      part[0] = __uint_as_float((cu[s].d[0] ^ cu[s].d[1] ^ cu[s].d[2]) & 0x3f000000u) + sf[s] + zz[s + 8];
+#else
+      score_steps<G, RB, TB, 0>(cu[s], lut_row0, sf, zz, part);
+#endif
       if constexpr (G == 4) {
-        sc[i] = tsum16(tsum32(part[0], part[2]), tsum32(part[1], part[3]));
+        sc[s] = tsum16(tsum32(part[0], part[2]), tsum32(part[1], part[3]));
       } else if constexpr (G == 2) {
         const float b = tsum32(part[0], part[1]);
-        sc[i] = tsum16(b, b);
+        sc[s] = tsum16(b, b);
       } else {
-        sc[i] = sum_rows(part[0]);
+        sc[s] = sum_rows(part[0]);
       }
     }
 
     // ---- online softmax over the page (log2 domain) ----
     float pm = kNegInf;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int tok = i * 16 + col;
+    for (int t = 0; t < 8; ++t) {
+      const int tok = t * 16 + col;
       if constexpr (SCORES) {
-        if (owner && tok < nv)
+        if (owner && tok < nv_cur)
           a.scores[(static_cast<int64_t>(seq) * a.n_q_heads + kvh * G + my_head) * a.scores_stride +
-                   static_cast<int64_t>(pi) * kGroup + tok] = sc[i];
+                   static_cast<int64_t>(pi) * kGroup + tok] = sc[t];
       }
-      sc[i] = (tok < nv) ? sc[i] * a.scale_log2 : kNegInf;
-      pm = fmaxf(pm, sc[i]);
+      sc[t] = (tok < nv_cur) ? sc[t] * a.scale_log2 : kNegInf;
+      pm = fmaxf(pm, sc[t]);
     }
     pm = row_max(pm);
     const float m_new = fmaxf(m_run, pm);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);     // 0 on the first page
+    const bool dead = !(m_new > kNegInf);                          // nothing valid seen so far
+    const float alpha = dead ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first page
     float psum = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float p = __builtin_amdgcn_exp2f(sc[i] - m_new);
+    for (int t = 0; t < 8; ++t) {
+      const float p = dead ? 0.f : __builtin_amdgcn_exp2f(sc[t] - m_new);
       psum += p;
-      if (owner) pw[(i * 16 + col) * G + my_head] = p;
+      if (owner) *(PQ_LDS float*)static_cast<uintptr_t>(pw_addr + ((t * 16 + col) * G + my_head) * 4) = p;
     }
     l_run = fmaf(l_run, alpha, psum);
     m_run = m_new;
     if (owner && col == 0) alpha_s[wave][my_head] = alpha;
     wave_lds_sync();
 
+    // ---- next page's parameters and codes, into the registers the score phase released ----
+#pragma unroll
+    for (int v4 = 0; v4 < 4; ++v4) praw[v4] = buf_load16<kAuxCached>(rp_nxt, voff_params, v4 * 16);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) cu[s] = load_unit<W>(rc_nxt, voff_codes, s * 16 * UB);
+
     // ---- values: acc[h][:] = acc[h][:] * alpha_h + sum_n p_h[n] V[n][:] ----
     {
-      const float4 al4 = *reinterpret_cast<const float4*>(alpha_s[wave]);
+      const f32x4 al4 = *(const PQ_LDS f32x4*)static_cast<uintptr_t>(lds_addr(alpha_s[wave]));
       const float al[4] = {al4.x, al4.y, al4.z, al4.w};
 #pragma unroll
       for (int h = 0; h < G; ++h)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[h][e] *= al[h];
     }
-    consume_values<G>(vx, 0, pw_addr, row, acc);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) vx[i] = buf_load16<kAuxStream>(rs_values, voff_values, (16 + i) * 1024);
     __builtin_amdgcn_sched_barrier(0);
-    consume_values<G>(vy, 8, pw_addr, row, acc);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) vy[i] = buf_load16<kAuxStream>(rs_values, voff_values, (24 + i) * 1024);
-    __builtin_amdgcn_sched_barrier(0);
-    consume_values<G>(vx, 16, pw_addr, row, acc);
-    consume_values<G>(vy, 24, pw_addr, row, acc);
+    for (int k = 0; k < 8; ++k) {
+#ifdef PQ_EXP_NOCOMPUTE
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        acc[0][r] += __uint_as_float((ring[k & 3][r].x ^ ring[k & 3][r].y ^ ring[k & 3][r].z ^ ring[k & 3][r].w) & 0x3f000000u);
+#else
+      consume_values<G>(ring[k & 3], 4 * k, pw_addr, row, acc);
+#endif
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (k < 4) ring[k & 3][r] = buf_load16<kAuxStream>(rv_cur, voff_values, (16 + 4 * k + r) * 1024);
+        else       ring[k & 3][r] = buf_load16<kAuxStream>(rv_nxt, voff_values, (4 * (k - 4) + r) * 1024);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
     wave_lds_sync();   // the next page overwrites prob[] / alpha_s[]
+    rc_cur = rc_nxt; rp_cur = rp_nxt; rv_cur = rv_nxt; nv_cur = nv_nxt;
   }
 
   // ---- fold the four wavefronts into one partial per query head ----
