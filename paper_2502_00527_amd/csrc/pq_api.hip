@@ -29,7 +29,10 @@ bool layout_supported(const pq_layout* l) {
 ChunkPlan plan_chunks(int32_t n_seqs, int32_t n_kv_heads, int32_t max_seq_len) {
   const int64_t max_pages = (static_cast<int64_t>(max_seq_len) + kGroup - 1) / kGroup;
   const int64_t units = static_cast<int64_t>(n_seqs) * n_kv_heads;
-  constexpr int64_t kWantGroups = 2048;
+#ifndef PQ_WANT_GROUPS
+#define PQ_WANT_GROUPS 2048
+#endif
+  constexpr int64_t kWantGroups = PQ_WANT_GROUPS;
   int32_t ppc = 32;
   while (ppc > 4 && units * ((max_pages + ppc - 1) / ppc) < kWantGroups) ppc >>= 1;
   ChunkPlan p;
