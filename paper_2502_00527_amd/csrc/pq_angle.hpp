@@ -1,0 +1,72 @@
+// Angle bin of the uniform t-bit grid over [-pi, pi) (paper Section 3.2 with a uniform grid):
+// the code is floor((atan2(y, x) + pi) * 2^t / (2 pi)) evaluated as in exact arithmetic, without
+// an arc tangent.  Plain C++ (host and device) so that the rule can also be checked on the CPU.
+//
+// The grid is cut into eight octants that start on an axis or a diagonal.  The octant follows
+// from sign and magnitude comparisons, which are exact, so a point exactly on an octant boundary
+// lands in the octant that STARTS there (bins are half-open arcs; these are the only directions
+// where a float pair can sit exactly on a bin edge, because the other edges have irrational
+// slopes).  Inside an octant the 2^t / 8 bins are separated by the slopes tan(k D), D = 2 pi / 2^t:
+// the bin is a count of float64 comparisons against mx * tan(k D) (mn, mx = the smaller / larger
+// of |x|, |y|), whose rounding moves an edge by ~1e-16 rad.  In odd octants the angle runs against
+// the ratio mn / mx, so the count is taken from the other side.
+// Conventions: x = y = 0 -> bin 2^(t-1) (theta = 0); y = +0, x < 0 (theta = +pi) -> last bin;
+// y = -0, x < 0 (theta = -pi) -> bin 0.
+#pragma once
+
+#include <math.h>
+#include <stdint.h>
+
+#ifndef PQ_HD
+#define PQ_HD
+#endif
+
+namespace pq {
+
+// tan_edge[k] = tan(k * 2 pi / 2^t) for 1 <= k < 2^t / 8 (unused entries are ignored)
+template <int TB>
+PQ_HD inline uint32_t angle_bin(float x, float y, const double* tan_edge) {
+  constexpr int NB = 1 << TB;
+  constexpr int S = NB >= 8 ? NB / 8 : 1;           // bins per octant
+  // Everything about the octant is integer arithmetic on the IEEE bit patterns (finite inputs):
+  // magnitudes compare like unsigned integers, and 0/1 flags are combined without branches.
+  uint32_t bx, by;
+  __builtin_memcpy(&bx, &x, 4);
+  __builtin_memcpy(&by, &y, 4);
+  const uint32_t ax = bx & 0x7fffffffu, ay = by & 0x7fffffffu;
+  const uint32_t xnz = (ax + 0x7fffffffu) >> 31, ynz = (ay + 0x7fffffffu) >> 31;   // 1 if non-zero
+  const uint32_t xn = (bx >> 31) & xnz;                      // x < 0
+  const uint32_t yn = (by >> 31) & (ynz | xn);               // y < 0, or y = -0 with x < 0 (theta = -pi)
+  const uint32_t lt = (ay - ax) >> 31, gt = (ax - ay) >> 31; // |y| < |x|, |y| > |x|
+  // octant:
+  //   lower half plane (yn): x < 0 -> 0 | 1 (the diagonal starts 1); x = 0 -> 2; x > 0 -> 2 | 3
+  //   upper half plane     : x > 0 -> 4 | 5;                         x = 0 -> 6; x < 0 -> 6 | 7
+  const uint32_t same = 1u ^ xn ^ yn;
+  const uint32_t within_nz = same * (1u - lt) + (1u ^ same) * (3u - gt);
+  const uint32_t within = xnz * within_nz + (1u ^ xnz) * 2u;
+  const uint32_t o = (1u ^ yn) * 4u + within;
+  uint32_t code;
+  if (TB == 2) {
+    code = o >> 1;                                  // bins are quadrants
+  } else {
+    uint32_t sub = 0;
+    if (S > 1) {
+      const uint32_t mnb = ax < ay ? ax : ay, mxb = ax < ay ? ay : ax;
+      float mnf, mxf;
+      __builtin_memcpy(&mnf, &mnb, 4);
+      __builtin_memcpy(&mxf, &mxb, 4);
+      const double mn = mnf, mx = mxf;
+      const uint32_t odd = o & 1u;
+      for (int k = 1; k < S; ++k) {
+        const double edge = mx * tan_edge[k];
+        const uint32_t past_odd = mn <= edge, past_even = edge <= mn;
+        sub += odd * past_odd + (1u ^ odd) * past_even;
+      }
+    }
+    code = o * S + sub;
+  }
+  const uint32_t origin = 1u ^ (xnz | ynz);
+  return origin * (NB / 2) + (1u ^ origin) * code;
+}
+
+}  // namespace pq

@@ -33,7 +33,10 @@ ChunkPlan plan_chunks(int32_t n_seqs, int32_t n_kv_heads, int32_t max_seq_len) {
 #define PQ_WANT_GROUPS 2048
 #endif
   constexpr int64_t kWantGroups = PQ_WANT_GROUPS;
-  int32_t ppc = 32;
+#ifndef PQ_MAX_PPC
+#define PQ_MAX_PPC 32
+#endif
+  int32_t ppc = PQ_MAX_PPC;
   while (ppc > 4 && units * ((max_pages + ppc - 1) / ppc) < kWantGroups) ppc >>= 1;
   ChunkPlan p;
   p.pages_per_chunk = ppc;

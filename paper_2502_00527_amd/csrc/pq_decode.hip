@@ -279,7 +279,10 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   __shared__ __attribute__((aligned(16))) float red_acc[kWaves][G][kHeadDim];
   __shared__ float red_ml[kWaves][G][2];
 
-  const int chunk = blockIdx.x, kvh = blockIdx.y, seq = blockIdx.z;
+  // Chunk-major launch order: the KV heads of one page are neighbours in memory and run
+  // together; every sequence's first chunks run first, and the chunks that only long sequences
+  // have (with the empty work-groups of the short ones) come last, which balances ragged batches.
+  const int kvh = blockIdx.x, seq = blockIdx.y, chunk = blockIdx.z;
   const int L = min(a.seq_lens[seq], a.max_seq_len);
   if (L <= 0) return;
   const int n_pages = (L + kGroup - 1) / kGroup;
@@ -530,34 +533,60 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   }
 }
 
-// out[seq][head][:] = sum_c 2^(m_c - M) acc_c / sum_c 2^(m_c - M) l_c over the
-// chunks the sequence really has; one work-group of 128 threads per (head, seq).
+// out[seq][head][:] = sum_c 2^(m_c - M) acc_c / sum_c 2^(m_c - M) l_c over the chunks the
+// sequence really has.  One work-group of 128 threads per (head, seq): thread = (chunk slice
+// tid / 32, dims 4 * (tid % 32) ..+3); the four slices take chunks c = slice, slice + 4, ...
+// with independent 128-bit loads and are folded through LDS.
 __global__ __launch_bounds__(kHeadDim) void pq_decode_merge_kernel(
     const float* __restrict__ ws_acc, const float* __restrict__ ws_ml,
     const int32_t* __restrict__ seq_lens, float* __restrict__ out, int32_t n_q_heads,
     int32_t max_seq_len, int32_t pages_per_chunk, int32_t n_chunks) {
-  const int head = blockIdx.x, seq = blockIdx.y, dim = threadIdx.x;
+  __shared__ float4 part_o[4][32];
+  __shared__ float part_l[4];
+  const int head = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x;
+  const int slice = tid >> 5, quad = tid & 31;
   const int L = min(seq_lens[seq], max_seq_len);
   const int64_t oh = static_cast<int64_t>(seq) * n_q_heads + head;
   if (L <= 0) {
-    out[oh * kHeadDim + dim] = 0.f;
+    out[oh * kHeadDim + tid] = 0.f;
     return;
   }
   const int n_pages = (L + kGroup - 1) / kGroup;
   const int nc = (n_pages + pages_per_chunk - 1) / pages_per_chunk;
-  const float* ml = ws_ml + oh * n_chunks * 2;
-  const float* ac = ws_acc + oh * n_chunks * kHeadDim + dim;
+  const float2* ml = reinterpret_cast<const float2*>(ws_ml) + oh * n_chunks;
+  const float4* ac = reinterpret_cast<const float4*>(ws_acc + oh * n_chunks * kHeadDim) + quad;
   float M = kNegInf;
-  for (int c = 0; c < nc; ++c) M = fmaxf(M, ml[2 * c]);
-  float o = 0.f, l = 0.f;
+#pragma unroll 4
+  for (int c = 0; c < nc; ++c) M = fmaxf(M, ml[c].x);
+  float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+  float l = 0.f;
   if (M > kNegInf) {
-    for (int c = 0; c < nc; ++c) {
-      const float w = __builtin_amdgcn_exp2f(ml[2 * c] - M);
-      o = fmaf(w, ac[static_cast<int64_t>(c) * kHeadDim], o);
-      l = fmaf(w, ml[2 * c + 1], l);
+#pragma unroll 4
+    for (int c = slice; c < nc; c += 4) {
+      const float2 mlc = ml[c];
+      const float4 v = ac[static_cast<int64_t>(c) * (kHeadDim / 4)];
+      const float w = __builtin_amdgcn_exp2f(mlc.x - M);
+      o.x = fmaf(w, v.x, o.x);
+      o.y = fmaf(w, v.y, o.y);
+      o.z = fmaf(w, v.z, o.z);
+      o.w = fmaf(w, v.w, o.w);
+      l = fmaf(w, mlc.y, l);
     }
   }
-  out[oh * kHeadDim + dim] = (l > 0.f) ? o / l : 0.f;
+  part_o[slice][quad] = o;
+  if (quad == 0) part_l[slice] = l;
+  __syncthreads();
+  if (slice == 0) {
+    const float lt = part_l[0] + part_l[1] + part_l[2] + part_l[3];
+    float4 r = part_o[0][quad];
+#pragma unroll
+    for (int s2 = 1; s2 < 4; ++s2) {
+      const float4 t = part_o[s2][quad];
+      r.x += t.x; r.y += t.y; r.z += t.z; r.w += t.w;
+    }
+    const float inv = lt > 0.f ? 1.f / lt : 0.f;
+    reinterpret_cast<float4*>(out + oh * kHeadDim)[quad] = make_float4(r.x * inv, r.y * inv, r.z * inv, r.w * inv);
+  }
 }
 
 struct Workspace {
@@ -605,7 +634,7 @@ int check_decode_shape(const pq_layout* l, int32_t n_seqs, int32_t n_q_heads, in
   if (!layout_supported(l)) return PQ_ERR_UNSUPPORTED;
   const int G = n_q_heads / l->n_kv_heads;
   if (G != 1 && G != 2 && G != 4) return PQ_ERR_UNSUPPORTED;
-  if (n_seqs > 65535 || l->n_kv_heads > 65535 || n_q_heads > 65535) return PQ_ERR_UNSUPPORTED;
+  if (n_seqs > 65535 || n_q_heads > 65535) return PQ_ERR_UNSUPPORTED;   // grid.y, merge grid.x
   return PQ_OK;
 }
 
@@ -670,7 +699,7 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
     a.sin_tab[s] = s < nb ? static_cast<float>(sin(th)) : 0.f;
   }
 
-  const dim3 grid(plan.n_chunks, layout->n_kv_heads, n_seqs);
+  const dim3 grid(layout->n_kv_heads, n_seqs, plan.n_chunks);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const int G = n_q_heads / layout->n_kv_heads;
   hipError_t e = hipSuccess;

@@ -9,11 +9,12 @@
 // the arithmetic that leads to them is pinned:
 //   * rho, (rho - z) / s: IEEE fp32, one rounding per operation, no fused
 //     multiply-add (this file is compiled with floating-point contraction off).
-//   * the angle bin is decided by the sign of exact-to-1e-16 float64 cross
-//     products against the two neighbouring bin-edge directions, so it equals
-//     the floor of the real-number quotient; a point exactly on an edge (only
-//     possible on an axis or a diagonal) belongs to the upper bin, theta = +pi
-//     is clamped into the last bin, and x = y = 0 goes to bin 2^(t-1).
+//   * the angle bin is decided by exact sign/magnitude comparisons (octant)
+//     and float64 slope comparisons against the bin edges inside the octant,
+//     so it equals the floor of the real-number quotient; a point exactly on
+//     an edge (only possible on an axis or a diagonal) belongs to the upper
+//     bin, theta = +pi is clamped into the last bin, and x = y = 0 goes to
+//     bin 2^(t-1).
 //
 // One work-group encodes one page (128 tokens) of one KV head: thread =
 // (pair octet o = tid % 8, token slot tid / 8), four tokens per thread.
@@ -23,6 +24,8 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 
+#define PQ_HD __host__ __device__
+#include "pq_angle.hpp"
 #include "pq_internal.hpp"
 
 namespace pq {
@@ -41,9 +44,7 @@ struct EncodeArgs {
   int64_t n_tokens;
   int64_t n_pool_pages;
   int32_t n_kv_heads;
-  float bins_per_radian;                 // 2^t / (2 pi)
-  double edge_cos[kMaxAngleBins + 1];    // direction of bin edge k: angle -pi + k * 2 pi / 2^t
-  double edge_sin[kMaxAngleBins + 1];
+  double tan_edge[kMaxAngleBins / 8];    // tan(k * 2 pi / 2^t) for the edges inside an octant
 };
 
 __device__ __forceinline__ void load8(const __half* p, float (&v)[8]) {
@@ -62,20 +63,29 @@ __device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
   v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
 }
 
-template <int TB>
-__device__ __forceinline__ uint32_t angle_code(float x, float y, const EncodeArgs& a) {
-  constexpr int NB = 1 << TB;
-  if (x == 0.f && y == 0.f) return NB / 2;
-  // first guess in fp32 (within one bin of the truth) ...
-  int k = static_cast<int>(floorf((atan2f(y, x) + 3.14159265358979f) * a.bins_per_radian));
-  k = max(0, min(NB - 1, k));
-  // ... settled by which side of the neighbouring edges the point lies on
-  const double xd = x, yd = y;
-  const double lo = a.edge_cos[k] * yd - a.edge_sin[k] * xd;          // >= 0: at or past edge k
-  const double hi = a.edge_cos[k + 1] * yd - a.edge_sin[k + 1] * xd;  // >= 0: at or past edge k+1
-  if (lo < 0.0) k -= 1;
-  else if (hi >= 0.0) k += 1;
-  return static_cast<uint32_t>(max(0, min(NB - 1, k)));
+// Correctly rounded fp32 square root.  For fp32 inputs this is the compiler's sequence (it also
+// covers denormal and infinite arguments).  A sum of two squares of fp16 values is either 0 or at
+// least 2^-48 and at most 2^33, so the hardware approximation (1 ulp) only needs the final
+// rounding fix: step to the neighbour whose exact residual has the right sign.
+template <typename KT>
+__device__ __forceinline__ float sqrt_rn(float s) {
+  if constexpr (sizeof(KT) == 4) {
+    return sqrtf(s);
+  } else {
+    const float r = __builtin_amdgcn_sqrtf(s);
+    const float dn = __uint_as_float(__float_as_uint(r) - 1u), up = __uint_as_float(__float_as_uint(r) + 1u);
+    const float e_dn = __builtin_fmaf(-dn, r, s), e_up = __builtin_fmaf(-up, r, s);
+    float out = e_dn <= 0.f ? dn : r;
+    out = e_up > 0.f ? up : out;
+    return s == 0.f ? 0.f : out;
+  }
+}
+// min / max of non-negative floats through their bit patterns (no NaN canonicalisation needed)
+__device__ __forceinline__ float min_nonneg(float p, float q) {
+  return __uint_as_float(min(__float_as_uint(p), __float_as_uint(q)));
+}
+__device__ __forceinline__ float max_nonneg(float p, float q) {
+  return __uint_as_float(max(__float_as_uint(p), __float_as_uint(q)));
 }
 
 template <int RB, int TB, typename KT>
@@ -100,7 +110,7 @@ __global__ __launch_bounds__(kEncThreads) void pq_encode_kernel(const EncodeArgs
   uint32_t ang[kItems][2];        // 8 angle codes, one byte each
   float mn[8], mx[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) { mn[e] = INFINITY; mx[e] = -INFINITY; }
+  for (int e = 0; e < 8; ++e) { mn[e] = INFINITY; mx[e] = 0.f; }
 
   const KT* base = static_cast<const KT*>(a.keys) + kvh * a.head_stride + o * 8;
 #pragma unroll
@@ -116,11 +126,11 @@ __global__ __launch_bounds__(kEncThreads) void pq_encode_kernel(const EncodeArgs
       for (int e = 0; e < 8; ++e) {
         const float xx = x[e] * x[e];
         const float yy = y[e] * y[e];
-        const float r = sqrtf(xx + yy);   // correctly rounded (the fast-sqrt intrinsic is not)
+        const float r = sqrt_rn<KT>(xx + yy);
         rho[it][e] = r;
-        mn[e] = fminf(mn[e], r);
-        mx[e] = fmaxf(mx[e], r);
-        ang[it][e >> 2] |= angle_code<TB>(x[e], y[e], a) << (8 * (e & 3));
+        mn[e] = min_nonneg(mn[e], r);
+        mx[e] = max_nonneg(mx[e], r);
+        ang[it][e >> 2] |= angle_bin<TB>(x[e], y[e], a.tan_edge) << (8 * (e & 3));
       }
     } else {
 #pragma unroll
@@ -133,8 +143,8 @@ __global__ __launch_bounds__(kEncThreads) void pq_encode_kernel(const EncodeArgs
   for (int e = 0; e < 8; ++e) {
 #pragma unroll
     for (int m = 8; m < 64; m <<= 1) {
-      mn[e] = fminf(mn[e], __shfl_xor(mn[e], m));
-      mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], m));
+      mn[e] = min_nonneg(mn[e], __shfl_xor(mn[e], m));
+      mx[e] = max_nonneg(mx[e], __shfl_xor(mx[e], m));
     }
   }
   if ((tid & 63) < 8) {
@@ -153,8 +163,8 @@ __global__ __launch_bounds__(kEncThreads) void pq_encode_kernel(const EncodeArgs
     float lo = s_mn[0][o * 8 + e], hi = s_mx[0][o * 8 + e];
 #pragma unroll
     for (int w = 1; w < kEncThreads / 64; ++w) {
-      lo = fminf(lo, s_mn[w][o * 8 + e]);
-      hi = fmaxf(hi, s_mx[w][o * 8 + e]);
+      lo = min_nonneg(lo, s_mn[w][o * 8 + e]);
+      hi = max_nonneg(hi, s_mx[w][o * 8 + e]);
     }
     const float s32 = (hi - lo) * (1.0f / static_cast<float>(1 << RB));   // exact scaling by 2^-r
     const __half sh = __float2half_rn(s32), zh = __float2half_rn(lo);      // stored in 16 bits (Appendix B.1)
@@ -178,11 +188,9 @@ __global__ __launch_bounds__(kEncThreads) void pq_encode_kernel(const EncodeArgs
     if (tok < nv) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        float qf = 0.f;
-        if (sf[e] != 0.f) {
-          qf = floorf((rho[it][e] - zf[e]) / sf[e]);        // IEEE division
-          qf = fminf(fmaxf(qf, 0.f), static_cast<float>((1 << RB) - 1));
-        }
+        float qf = floorf((rho[it][e] - zf[e]) / sf[e]);    // IEEE division
+        qf = fminf(fmaxf(qf, 0.f), static_cast<float>((1 << RB) - 1));
+        qf = sf[e] != 0.f ? qf : 0.f;                       // constant group: code 0 (also drops the NaN of 0/0)
         const uint32_t ac = (ang[it][e >> 2] >> (8 * (e & 3))) & 0xffu;
         const uint64_t sym = (static_cast<uint64_t>(ac) << RB) | static_cast<uint32_t>(qf);
         bits |= sym << (e * W);
@@ -249,28 +257,8 @@ extern "C" int pq_encode_keys(const pq_layout* layout, const void* keys, pq_dtyp
   a.n_pool_pages = n_pool_pages;
   a.n_kv_heads = layout->n_kv_heads;
   const int nb = 1 << layout->t_bits;
-  a.bins_per_radian = static_cast<float>(nb / (2.0 * M_PI));
-  for (int k = 0; k <= kMaxAngleBins; ++k) {
-    double c = 0.0, s = 0.0;
-    if (k <= nb) {
-      const double e = -M_PI + (k % nb) * (2.0 * M_PI / nb);
-      c = cos(e);
-      s = sin(e);
-      // edges on an axis or a diagonal are exact directions, so that a point
-      // exactly on them gives a cross product of exactly zero
-      if (fabs(c) < 1e-12) c = 0.0;
-      if (fabs(s) < 1e-12) s = 0.0;
-      if (c == 0.0) s = s > 0 ? 1.0 : -1.0;
-      if (s == 0.0) c = c > 0 ? 1.0 : -1.0;
-      if (fabs(fabs(c) - fabs(s)) < 1e-12) {
-        const double r = sqrt(0.5);
-        c = c > 0 ? r : -r;
-        s = s > 0 ? r : -r;
-      }
-    }
-    a.edge_cos[k] = c;
-    a.edge_sin[k] = s;
-  }
+  for (int k = 0; k < kMaxAngleBins / 8; ++k)
+    a.tan_edge[k] = (k >= 1 && k < nb / 8) ? tan(k * (2.0 * M_PI / nb)) : 0.0;
 
   const dim3 grid(static_cast<uint32_t>(n_groups), layout->n_kv_heads);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);

@@ -1,0 +1,64 @@
+"""The library's angle-bin rule (csrc/pq_angle.hpp), built for the CPU, against the oracle:
+random pairs, every axis / diagonal tie, signed zeros, subnormals, fp16-grid values."""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+from oracle import polar
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def host_lib(tmp_path_factory):
+    out = tmp_path_factory.mktemp("anglehost") / "libangle_host.so"
+    src = os.path.join(ROOT, "tests", "host", "angle_bin_host.cpp")
+    inc = os.path.join(ROOT, "paper_2502_00527_amd", "csrc")
+    subprocess.run(["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-shared", "-fPIC", "-I", inc, src,
+                    "-o", str(out)], check=True)
+    lib = ctypes.CDLL(str(out))
+    lib.angle_bins_host.restype = ctypes.c_int
+    lib.angle_bins_host.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
+    return lib
+
+
+def _host_bins(lib, x, y, t):
+    x = np.ascontiguousarray(x, np.float32)
+    y = np.ascontiguousarray(y, np.float32)
+    out = np.empty(x.size, np.int32)
+    assert lib.angle_bins_host(x.ctypes.data, y.ctypes.data, x.size, t, out.ctypes.data) == 0
+    return out
+
+
+def _inputs():
+    rng = np.random.default_rng(77)
+    xs, ys = [], []
+    # random float32 and fp16-grid pairs (fp16 pairs hit |x| == |y| about 5e-4 of the time)
+    xs.append(rng.standard_normal(200000).astype(np.float32)); ys.append(rng.standard_normal(200000).astype(np.float32))
+    h = rng.standard_normal((2, 400000)).astype(np.float16).astype(np.float32)
+    xs.append(h[0]); ys.append(h[1])
+    # exact ties at many magnitudes, with both signs of zero
+    mags = np.array([2.0 ** e for e in range(-24, 16, 3)] + [3.0, 0.1, 65504.0, 5.9604645e-08], np.float32)
+    dirs = [(1, 0), (1, 1), (0, 1), (-1, 1), (-1, 0), (-1, -1), (0, -1), (1, -1), (0, 0),
+            (-1, -0.0), (1, -0.0), (-0.0, 1), (-0.0, -1), (-0.0, -0.0), (-0.0, 0.0), (0.0, -0.0)]
+    for dx, dy in dirs:
+        xs.append(np.float32(dx) * mags); ys.append(np.float32(dy) * mags)
+    # coarse integer lattice: many near-edge and on-edge directions
+    g = np.arange(-12, 13, dtype=np.float32)
+    gx, gy = np.meshgrid(g, g)
+    xs.append(gx.ravel()); ys.append(gy.ravel())
+    return np.concatenate(xs), np.concatenate(ys)
+
+
+@pytest.mark.parametrize("t", [2, 3, 4, 5])
+def test_angle_rule_matches_oracle(host_lib, t):
+    x, y = _inputs()
+    want, edge = polar.angle_bin(x, y, t)
+    got = _host_bins(host_lib, x, y, t)
+    bad = got != want
+    # the two float64 evaluations may differ only within ~1e-15 rad of an irrational edge
+    assert not np.any(bad & (edge > 1e-12)), (x[bad][:5], y[bad][:5], got[bad][:5], want[bad][:5])
+    assert bad.sum() <= 2

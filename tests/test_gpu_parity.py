@@ -151,6 +151,34 @@ def test_results_are_deterministic():
     assert torch.equal(oa, ob)
 
 
+def test_block_table_entry_outside_pool_is_masked():
+    """A page id outside the pool makes that page count as masked: nothing is read for it and the
+    result is attention over the remaining tokens."""
+    from oracle import attention
+    from paper_2502_00527_amd.cache import build_device_cache
+
+    wl = WL["gqa"].scaled(n_seqs=2, n_q_heads=8, n_kv_heads=2, max_len=1100, min_len=1100)
+    cache = build_device_cache(wl)
+    bad_seq, bad_page = 1, 3
+    bt = cache.block_table.clone()
+    bt[bad_seq, bad_page] = cache.n_pool_pages + 7
+    bt[0, 0] = -5
+    cache.block_table = bt
+    _say("[parity] masked_page: decode launch")
+    out = cache.decode().cpu().numpy()
+    torch.cuda.synchronize()
+    q_h = W.queries(wl)
+    g = wl.group_tokens
+    for s, page in ((0, 0), (bad_seq, bad_page)):
+        ref = OracleSeq(wl, s, 1100)
+        _, _, k_hat = ref.attend(q_h[s], cache.sm_scale)
+        keep = np.ones(1100, bool)
+        keep[page * g:(page + 1) * g] = False
+        v = W.values_for_seq(wl, s, 1100).astype(np.float64)
+        _, want = attention.attend(q_h[s].astype(np.float64), k_hat[keep], v[keep], cache.sm_scale)
+        assert np.abs(out[s] - want).max() <= OUT_ABS
+
+
 # ---- full-size launch configurations (what the benchmark times), sampled sequences ----
 
 FULL = {
