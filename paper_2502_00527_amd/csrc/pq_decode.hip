@@ -294,22 +294,6 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-  // ---- table of the G query heads that share this KV head (Section 3.3) ----
-  {
-    const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * G) * kHeadDim;
-    float* lf = reinterpret_cast<float*>(lut);
-    for (int idx = tid; idx < kPairs * NA; idx += kThreads) {
-      const int j = idx >> TB, s = idx & (NA - 1);
-      const float cs = a.cos_tab[s], sn = a.sin_tab[s];
-#pragma unroll
-      for (int h = 0; h < G; ++h) {
-        const float qx = static_cast<float>(qb[h * kHeadDim + j]);
-        const float qy = static_cast<float>(qb[h * kHeadDim + j + kPairs]);
-        lf[idx * 4 + h] = fmaf(qx, cs, qy * sn);
-      }
-    }
-  }
-  __syncthreads();
 
   const int row = lane >> 4;             // score phase: pair block; value phase: token slot
   const int col = lane & 15;             // score phase: token in the pass; value phase: dim slice
@@ -379,6 +363,24 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) ring[k][r] = buf_load16<kAuxStream>(rv_cur, voff_values, (4 * k + r) * 1024);
   }
+
+  // ---- table of the G query heads that share this KV head (Section 3.3) ----
+  // (built while the first page's loads, issued above, are in flight)
+  {
+    const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * G) * kHeadDim;
+    float* lf = reinterpret_cast<float*>(lut);
+    for (int idx = tid; idx < kPairs * NA; idx += kThreads) {
+      const int j = idx >> TB, s = idx & (NA - 1);
+      const float cs = a.cos_tab[s], sn = a.sin_tab[s];
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const float qx = static_cast<float>(qb[h * kHeadDim + j]);
+        const float qy = static_cast<float>(qb[h * kHeadDim + j + kPairs]);
+        lf[idx * 4 + h] = fmaf(qx, cs, qy * sn);
+      }
+    }
+  }
+  __syncthreads();
 
   for (int i = 0; i < n_w; ++i) {
     const int pi = page0 + wave + kWaves * i;                      // chunk-relative page of iteration i
