@@ -154,6 +154,25 @@ def main() -> int:
     ms_partials = time_region(partials_only, args.steps, torch)
     ms_merge = time_region(merge_only, args.steps, torch)
 
+    # the query-key product alone (pq_score_keys): the one operation the paper itself times
+    # (Section 5.2, batch 8); context beside the headline, not part of `value`
+    qk = None
+    if wl.n_seqs >= 8:
+        scores = torch.empty((8, wl.n_q_heads, cache.max_seq_len), dtype=torch.float32, device="cuda:0")
+        q8, bt8, sl8 = cache.q[:8].contiguous(), cache.block_table[:8].contiguous(), cache.seq_lens[:8].contiguous()
+
+        def qk_only():
+            pq.pq_score_keys(cache.layout, q8, cache.codes, cache.params, bt8, sl8, cache.max_seq_len, scores)
+
+        for _ in range(args.warmup):
+            qk_only()
+        ms_qk = time_region(qk_only, args.steps, torch)
+        n_scores = int(lens[:8].astype(np.int64).sum()) * wl.n_q_heads
+        qk = {"entry_point": "pq_score_keys", "batch": 8, "ms_per_call": ms_qk,
+              "scores_per_s": n_scores / (ms_qk * 1e-3),
+              "note": "paper Table 2 (hardware not stated): PolarQuant44 at batch 8 x 32K = 1.49 s per 10K calls"}
+        del scores
+
     # what this device streams with plain 128-bit loads (context for the roofline fraction)
     probe = torch.empty(2 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
     sink = torch.zeros(64, dtype=torch.int32, device="cuda:0")
@@ -188,6 +207,8 @@ def main() -> int:
                      "whole_step_GBps": alg_bytes / (ms_step * 1e-3) / 1e9},
         "wall_s_timed_region": wall,
     }
+    if qk is not None:
+        result["qk_only"] = qk
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, lens, args.cpu_budget)
     print(json.dumps(result), flush=True)

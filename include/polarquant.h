@@ -163,6 +163,20 @@ int pq_decode_merge(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
                     const void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * pq_score_keys -- the query-key product alone: raw scores q . k~ of every cached token
+ * through the lookup table (Section 3.3, Appendix A).  This is the operation whose latency
+ * the paper reports in Section 5.2 (query-key multiplication kernel).  Arguments as in
+ * pq_decode_attention; `scores` (device fp32 [n_seqs][n_q_heads][scores_stride], scores_stride
+ * >= max_seq_len) receives the scores of tokens < seq_len, other elements are left untouched.
+ * No workspace is needed.
+ */
+int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
+                  int32_t n_q_heads, const void* codes_pool, const void* params_pool,
+                  int64_t n_pool_pages, const int32_t* block_table, int32_t max_pages_per_seq,
+                  const int32_t* seq_lens, int32_t max_seq_len, float* scores, int64_t scores_stride,
+                  void* hip_stream);
+
+/*
  * pq_probe_read_stream -- measurement aid, not part of the method: a plain
  * 128-bit-load streaming read of `bytes` (multiple of 16) device bytes that
  * XOR-folds them into sink[0..63] (device uint32[64], so the loads cannot be

@@ -21,7 +21,8 @@ __all__ = [
     "Layout", "PQ_F16", "PQ_F32", "PolarQuantError", "lib_path", "load_library",
     "pq_version", "pq_strerror", "pq_codes_bytes_per_page", "pq_params_bytes_per_page",
     "pq_values_bytes_per_page", "pq_decode_workspace_bytes", "pq_encode_keys",
-    "pq_decode_attention", "pq_decode_partials", "pq_decode_merge", "pq_probe_read_stream",
+    "pq_decode_attention", "pq_decode_partials", "pq_decode_merge", "pq_score_keys",
+    "pq_probe_read_stream",
 ]
 
 PQ_F16, PQ_F32 = 0, 1
@@ -64,6 +65,8 @@ _SIGNATURES = {
                                    c_int64, c_void_p, c_size_t, c_void_p]),
     "pq_decode_merge": (c_int, [_LP, c_int32, c_int32, c_void_p, c_int32, c_void_p, c_void_p, c_size_t,
                                 c_void_p]),
+    "pq_score_keys": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_int64, c_void_p,
+                              c_int32, c_void_p, c_int32, c_void_p, c_int64, c_void_p]),
     "pq_probe_read_stream": (c_int, [c_void_p, c_size_t, c_void_p, c_void_p]),
 }
 
@@ -209,6 +212,22 @@ def pq_decode_merge(layout: Layout, n_seqs: int, n_q_heads: int, seq_lens, max_s
         _dev_ptr(out, "out", (torch.float32,)), _dev_ptr(workspace, "workspace"),
         workspace.numel() * workspace.element_size(), _stream())
     _check(st, "pq_decode_merge")
+
+
+def pq_score_keys(layout: Layout, q, codes_pool, params_pool, block_table, seq_lens, max_seq_len: int,
+                  scores) -> None:
+    """Raw q . k~ of every cached token; `scores` fp32 [n_seqs, n_q_heads, stride >= max_seq_len]."""
+    import torch
+    if q.dim() != 3 or q.shape[2] != layout.head_dim:
+        raise PolarQuantError("q must be [n_seqs, n_q_heads, head_dim]")
+    n_pool_pages = codes_pool.numel() * codes_pool.element_size() // max(1, pq_codes_bytes_per_page(layout))
+    st = load_library().pq_score_keys(
+        ctypes.byref(layout), _dev_ptr(q, "q"), _float_kind(q, "q"), q.shape[0], q.shape[1],
+        _dev_ptr(codes_pool, "codes_pool"), _dev_ptr(params_pool, "params_pool"), n_pool_pages,
+        _dev_ptr(block_table, "block_table", (torch.int32,)), block_table.shape[1],
+        _dev_ptr(seq_lens, "seq_lens", (torch.int32,)), max_seq_len,
+        _dev_ptr(scores, "scores", (torch.float32,)), scores.shape[-1], _stream())
+    _check(st, "pq_score_keys")
 
 
 def pq_probe_read_stream(src, sink) -> None:

@@ -591,6 +591,137 @@ __global__ __launch_bounds__(kHeadDim) void pq_decode_merge_kernel(
   }
 }
 
+// ---- query-key scores only (the kernel the paper times in Section 5.2) ------------------
+// Same table, same page walk and same pair steps as the attention kernel, without softmax and
+// values: every wavefront scores its pages and stores the raw q . k~ of valid tokens.
+template <int G, int RB, int TB, typename QT>
+__global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArgs a) {
+  constexpr int W = RB + TB;
+  constexpr int UB = 2 * W;
+  constexpr int NA = 1 << TB;
+  constexpr int ROW = NA * 16;
+  __shared__ __attribute__((aligned(16))) uint8_t lut[kPairs * ROW];
+
+  const int kvh = blockIdx.x, seq = blockIdx.y, chunk = blockIdx.z;
+  const int L = min(a.seq_lens[seq], a.max_seq_len);
+  if (L <= 0) return;
+  const int n_pages = (L + kGroup - 1) / kGroup;
+  const int page0 = chunk * a.pages_per_chunk;
+  if (page0 >= n_pages) return;
+  const int npg = min(a.pages_per_chunk, n_pages - page0);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int row = lane >> 4, col = lane & 15;
+  const int my_head = (G == 4) ? row : (G == 2 ? (row >> 1) : 0);
+  const bool owner = (G == 4) || (G == 2 && (row & 1) == 0) || (G == 1 && row == 0);
+  const uint32_t lut_row0 = lds_addr(lut) + row * (kPairsPerUnit * ROW);
+  const uint32_t voff_codes = (row * kGroup + col) * UB;
+  const uint32_t voff_params = row * (kPairsPerUnit * 4);
+  constexpr uint32_t kCodesBytes = kBlocks * kGroup * UB;
+
+  const int n_w = npg > wave ? (npg - wave + kWaves - 1) / kWaves : 0;
+  int pid_lane = -1;
+  if (lane < n_w) {
+    const int64_t pid = a.block_table[static_cast<int64_t>(seq) * a.max_pages_per_seq + page0 + wave + kWaves * lane];
+    if (pid >= 0 && pid < a.n_pool_pages) pid_lane = static_cast<int>(pid);
+  }
+  auto page_setup = [&](int k, __amdgpu_buffer_rsrc_t& rc, __amdgpu_buffer_rsrc_t& rp, int& nv) {
+    const int pid = __builtin_amdgcn_readlane(pid_lane, k);
+    const bool ok = pid >= 0;
+    const int64_t ph = ok ? static_cast<int64_t>(pid) * a.n_kv_heads + kvh : 0;
+    nv = ok ? min(kGroup, L - (page0 + wave + kWaves * k) * kGroup) : 0;
+    rc = make_rsrc(a.codes + ph * kCodesBytes, ok ? kCodesBytes : 0u);
+    rp = make_rsrc(a.params + ph * kPairs, ok ? kPairs * 4u : 0u);
+  };
+  const __amdgpu_buffer_rsrc_t rs_empty = make_rsrc(a.codes, 0u);
+  __amdgpu_buffer_rsrc_t rc_cur = rs_empty, rp_cur = rs_empty, rc_nxt = rs_empty, rp_nxt = rs_empty;
+  int nv_cur = 0, nv_nxt = 0;
+  uint4 praw[4];
+  Unit<W / 2> cu[8];
+  if (n_w > 0) {
+    page_setup(0, rc_cur, rp_cur, nv_cur);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) praw[i] = buf_load16<kAuxCached>(rp_cur, voff_params, i * 16);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) cu[i] = load_unit<W>(rc_cur, voff_codes, i * 16 * UB);
+  }
+  {
+    const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * G) * kHeadDim;
+    float* lf = reinterpret_cast<float*>(lut);
+    for (int idx = tid; idx < kPairs * NA; idx += kThreads) {
+      const int j = idx >> TB, s = idx & (NA - 1);
+      const float cs = a.cos_tab[s], sn = a.sin_tab[s];
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const float qx = static_cast<float>(qb[h * kHeadDim + j]);
+        const float qy = static_cast<float>(qb[h * kHeadDim + j + kPairs]);
+        lf[idx * 4 + h] = fmaf(qx, cs, qy * sn);
+      }
+    }
+  }
+  __syncthreads();
+
+  float* const out_row = a.scores + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * G + my_head) * a.scores_stride;
+  for (int i = 0; i < n_w; ++i) {
+    const int pi = page0 + wave + kWaves * i;
+    if (i + 1 < n_w) {
+      page_setup(i + 1, rc_nxt, rp_nxt, nv_nxt);
+    } else {
+      rc_nxt = rp_nxt = rs_empty;
+      nv_nxt = 0;
+    }
+    float sf[16], zz[16];
+#pragma unroll
+    for (int v4 = 0; v4 < 4; ++v4) {
+      const uint32_t w4[4] = {praw[v4].x, praw[v4].y, praw[v4].z, praw[v4].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const __half2 sz = *reinterpret_cast<const __half2*>(&w4[e]);
+        const float s = __low2float(sz), z = __high2float(sz);
+        sf[v4 * 4 + e] = s;
+        zz[v4 * 4 + e] = fmaf(0.5f, s, z);
+      }
+    }
+#pragma unroll
+    for (int v4 = 0; v4 < 4; ++v4) praw[v4] = buf_load16<kAuxCached>(rp_nxt, voff_params, v4 * 16);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      float part[G];
+#pragma unroll
+      for (int h = 0; h < G; ++h) part[h] = 0.f;
+      score_steps<G, RB, TB, 0>(cu[s], lut_row0, sf, zz, part);
+      cu[s] = load_unit<W>(rc_nxt, voff_codes, s * 16 * UB);       // next page's pass s
+      float sc;
+      if constexpr (G == 4) {
+        sc = tsum16(tsum32(part[0], part[2]), tsum32(part[1], part[3]));
+      } else if constexpr (G == 2) {
+        const float b = tsum32(part[0], part[1]);
+        sc = tsum16(b, b);
+      } else {
+        sc = sum_rows(part[0]);
+      }
+      const int tok = s * 16 + col;
+      if (owner && tok < nv_cur) out_row[static_cast<int64_t>(pi) * kGroup + tok] = sc;
+    }
+    rc_cur = rc_nxt; rp_cur = rp_nxt; nv_cur = nv_nxt;
+  }
+}
+
+template <int RB, int TB>
+hipError_t launch_scores(int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st) {
+#define PQ_LAUNCH_SCORES(GG)                                                                            \
+  if (qdt == PQ_F16) hipLaunchKernelGGL((pq_score_keys_kernel<GG, RB, TB, __half>), grid, dim3(kThreads), 0, st, a); \
+  else hipLaunchKernelGGL((pq_score_keys_kernel<GG, RB, TB, float>), grid, dim3(kThreads), 0, st, a)
+  switch (G) {
+    case 1: PQ_LAUNCH_SCORES(1); break;
+    case 2: PQ_LAUNCH_SCORES(2); break;
+    default: PQ_LAUNCH_SCORES(4); break;
+  }
+#undef PQ_LAUNCH_SCORES
+  return hipGetLastError();
+}
+
 struct Workspace {
   float* acc;
   float* ml;
@@ -627,6 +758,17 @@ hipError_t launch_partials_g(int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid
     case 1: return launch_partials<1, RB, TB>(a, qdt, grid, st);
     case 2: return launch_partials<2, RB, TB>(a, qdt, grid, st);
     default: return launch_partials<4, RB, TB>(a, qdt, grid, st);
+  }
+}
+
+// cos / sin of the centre of every angle bin of the uniform grid over [-pi, pi) (Section 3.2
+// mid-point reconstruction), evaluated in float64 on the host.
+void fill_angle_tables(DecodeArgs& a, int t_bits) {
+  const int nb = 1 << t_bits;
+  for (int s = 0; s < kMaxAngleBins; ++s) {
+    const double th = -M_PI + (s + 0.5) * (2.0 * M_PI / nb);
+    a.cos_tab[s] = s < nb ? static_cast<float>(cos(th)) : 0.f;
+    a.sin_tab[s] = s < nb ? static_cast<float>(sin(th)) : 0.f;
   }
 }
 
@@ -693,13 +835,7 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
   a.pages_per_chunk = plan.pages_per_chunk;
   a.n_chunks = plan.n_chunks;
   a.scale_log2 = static_cast<float>(static_cast<double>(sm_scale) * 1.4426950408889634074);
-  const int nb = 1 << layout->t_bits;
-  for (int s = 0; s < kMaxAngleBins; ++s) {
-    // centre of angle bin s of the uniform grid over [-pi, pi)
-    const double th = -M_PI + (s + 0.5) * (2.0 * M_PI / nb);
-    a.cos_tab[s] = s < nb ? static_cast<float>(cos(th)) : 0.f;
-    a.sin_tab[s] = s < nb ? static_cast<float>(sin(th)) : 0.f;
-  }
+  fill_angle_tables(a, layout->t_bits);
 
   const dim3 grid(layout->n_kv_heads, n_seqs, plan.n_chunks);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -750,4 +886,50 @@ extern "C" int pq_decode_attention(const pq_layout* layout, const void* q, pq_dt
   if (st != PQ_OK) return st;
   return pq_decode_merge(layout, n_seqs, n_q_heads, seq_lens, max_seq_len, out, workspace, workspace_bytes,
                          hip_stream);
+}
+
+extern "C" int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
+                             int32_t n_q_heads, const void* codes_pool, const void* params_pool,
+                             int64_t n_pool_pages, const int32_t* block_table, int32_t max_pages_per_seq,
+                             const int32_t* seq_lens, int32_t max_seq_len, float* scores,
+                             int64_t scores_stride, void* hip_stream) {
+  const int st = check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len);
+  if (st != PQ_OK) return st;
+  if (!q || !codes_pool || !params_pool || !block_table || !seq_lens || !scores) return PQ_ERR_INVALID_ARG;
+  if (q_dtype != PQ_F16 && q_dtype != PQ_F32) return PQ_ERR_INVALID_ARG;
+  if (n_pool_pages <= 0 || max_pages_per_seq <= 0 || scores_stride < max_seq_len) return PQ_ERR_INVALID_ARG;
+  const int64_t need_pages = (static_cast<int64_t>(max_seq_len) + kGroup - 1) / kGroup;
+  if (need_pages > max_pages_per_seq) return PQ_ERR_INVALID_ARG;
+  const ChunkPlan plan = plan_chunks(n_seqs, layout->n_kv_heads, max_seq_len);
+  DecodeArgs a = {};
+  a.q = q;
+  a.codes = static_cast<const uint8_t*>(codes_pool);
+  a.params = static_cast<const uint32_t*>(params_pool);
+  a.block_table = block_table;
+  a.seq_lens = seq_lens;
+  a.scores = scores;
+  a.scores_stride = scores_stride;
+  a.n_pool_pages = n_pool_pages;
+  a.n_kv_heads = layout->n_kv_heads;
+  a.n_q_heads = n_q_heads;
+  a.max_pages_per_seq = max_pages_per_seq;
+  a.max_seq_len = max_seq_len;
+  a.pages_per_chunk = plan.pages_per_chunk;
+  a.n_chunks = plan.n_chunks;
+  fill_angle_tables(a, layout->t_bits);
+  const dim3 grid(layout->n_kv_heads, n_seqs, plan.n_chunks);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const int G = n_q_heads / layout->n_kv_heads;
+  hipError_t e = hipSuccess;
+  switch (layout->r_bits * 10 + layout->t_bits) {
+    case 44: e = launch_scores<4, 4>(G, a, q_dtype, grid, stream); break;
+    case 33: e = launch_scores<3, 3>(G, a, q_dtype, grid, stream); break;
+    case 53: e = launch_scores<5, 3>(G, a, q_dtype, grid, stream); break;
+    case 35: e = launch_scores<3, 5>(G, a, q_dtype, grid, stream); break;
+    case 42: e = launch_scores<4, 2>(G, a, q_dtype, grid, stream); break;
+    case 24: e = launch_scores<2, 4>(G, a, q_dtype, grid, stream); break;
+    default: return PQ_ERR_UNSUPPORTED;
+  }
+  if (e != hipSuccess) return record_hip_error(e);
+  return PQ_OK;
 }

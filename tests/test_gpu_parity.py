@@ -151,6 +151,36 @@ def test_results_are_deterministic():
     assert torch.equal(oa, ob)
 
 
+@pytest.mark.parametrize("name", ["gqa_ragged_tail", "tiny33_fp32", "group_of_two", "ragged_pages", "bits_r5t3"])
+def test_score_keys_entry_point(name):
+    """pq_score_keys (the query-key product alone) against the oracle's dequantize-then-dot scores,
+    and against the scores pq_decode_attention reports for the same cache."""
+    from paper_2502_00527_amd import pq_score_keys
+    from paper_2502_00527_amd.cache import build_device_cache
+
+    wl, lens = SMALL[name]
+    cache = build_device_cache(wl, lens=lens)
+    S, Hq = wl.n_seqs, wl.n_q_heads
+    got = torch.full((S, Hq, cache.max_seq_len), float("nan"), dtype=torch.float32, device="cuda:0")
+    _say(f"[parity] score_keys {name}: launch")
+    pq_score_keys(cache.layout, cache.q, cache.codes, cache.params, cache.block_table, cache.seq_lens,
+                  cache.max_seq_len, got)
+    via_attention = torch.full_like(got, float("nan"))
+    cache.decode(scores=via_attention)
+    torch.cuda.synchronize()
+    q_h = W.queries(wl)
+    for s in range(S):
+        L = int(cache.lens[s])
+        if L <= 0:
+            continue
+        ref = OracleSeq(wl, s, L)
+        ref_scores, _, k_hat = ref.attend(q_h[s], cache.sm_scale)
+        err = score_errors(got[s, :, :L].cpu().numpy(), ref_scores, q_h[s], k_hat)
+        assert err.max() <= SCORE_REL
+        assert torch.equal(got[s, :, :L], via_attention[s, :, :L])
+        assert torch.isnan(got[s, :, L:]).all(), "scores past the sequence end must stay untouched"
+
+
 def test_block_table_entry_outside_pool_is_masked():
     """A page id outside the pool makes that page count as masked: nothing is read for it and the
     result is attention over the remaining tokens."""
