@@ -29,14 +29,8 @@ bool layout_supported(const pq_layout* l) {
 ChunkPlan plan_chunks(int32_t n_seqs, int32_t n_kv_heads, int32_t max_seq_len) {
   const int64_t max_pages = (static_cast<int64_t>(max_seq_len) + kGroup - 1) / kGroup;
   const int64_t units = static_cast<int64_t>(n_seqs) * n_kv_heads;
-#ifndef PQ_WANT_GROUPS
-#define PQ_WANT_GROUPS 2048
-#endif
-  constexpr int64_t kWantGroups = PQ_WANT_GROUPS;
-#ifndef PQ_MAX_PPC
-#define PQ_MAX_PPC 32
-#endif
-  int32_t ppc = PQ_MAX_PPC;
+  constexpr int64_t kWantGroups = 2048;   // 512 resident work-groups x 4 rounds; 1024 and 4096 measured slower
+  int32_t ppc = 32;
   while (ppc > 4 && units * ((max_pages + ppc - 1) / ppc) < kWantGroups) ppc >>= 1;
   ChunkPlan p;
   p.pages_per_chunk = ppc;

@@ -100,6 +100,12 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Tuning constants of the attention kernel (measured on MI355X): 4 quads of 4 value rows in
+// flight per wavefront (8 or 32 rows change nothing), and a register budget of 2 wavefronts
+// per SIMD -- 3 or 4 only fit with spills and run 1.5-2x slower.
+#ifndef PQ_RING_SETS
+#define PQ_RING_SETS 4
+#endif
 #ifndef PQ_WAVES_PER_EU
 #define PQ_WAVES_PER_EU 2
 #endif
@@ -119,9 +125,6 @@ constexpr int kAuxStream = 2;     // gfx950 cache-policy bit "nt"
 constexpr int kAuxCached = 0;
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
-#ifdef PQ_EXP_NOMEM
-  bytes = 0;
-#endif
   // raw buffer, 32-bit data format, no swizzle
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, static_cast<int>(bytes), 0x00020000);
 }
@@ -351,7 +354,8 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   int nv_cur = 0, nv_nxt = 0;
   uint4 praw[4];
   Unit<W / 2> cu[8];
-  uint4 ring[4][4];
+  constexpr int kRingSets = PQ_RING_SETS;                          // register quads of 4 value rows in flight
+  uint4 ring[kRingSets][4];
   if (n_w > 0) {
     page_setup(0, rc_cur, rp_cur, rv_cur, nv_cur);
 #pragma unroll
@@ -359,7 +363,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) cu[i] = load_unit<W>(rc_cur, voff_codes, i * 16 * UB);
 #pragma unroll
-    for (int k = 0; k < 4; ++k)
+    for (int k = 0; k < kRingSets; ++k)
 #pragma unroll
       for (int r = 0; r < 4; ++r) ring[k][r] = buf_load16<kAuxStream>(rv_cur, voff_values, (4 * k + r) * 1024);
   }
@@ -412,11 +416,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
       float part[G];
 #pragma unroll
       for (int h = 0; h < G; ++h) part[h] = 0.f;
-#ifdef PQ_EXP_NOCOMPUTE
-      part[0] = __uint_as_float((cu[s].d[0] ^ cu[s].d[1] ^ cu[s].d[2]) & 0x3f000000u) + sf[s] + zz[s + 8];
-#else
       score_steps<G, RB, TB, 0>(cu[s], lut_row0, sf, zz, part);
-#endif
       if constexpr (G == 4) {
         sc[s] = tsum16(tsum32(part[0], part[2]), tsum32(part[1], part[3]));
       } else if constexpr (G == 2) {
@@ -474,17 +474,13 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-#ifdef PQ_EXP_NOCOMPUTE
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-        acc[0][r] += __uint_as_float((ring[k & 3][r].x ^ ring[k & 3][r].y ^ ring[k & 3][r].z ^ ring[k & 3][r].w) & 0x3f000000u);
-#else
-      consume_values<G>(ring[k & 3], 4 * k, pw_addr, row, acc);
-#endif
+      consume_values<G>(ring[k % kRingSets], 4 * k, pw_addr, row, acc);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        if (k < 4) ring[k & 3][r] = buf_load16<kAuxStream>(rv_cur, voff_values, (16 + 4 * k + r) * 1024);
-        else       ring[k & 3][r] = buf_load16<kAuxStream>(rv_nxt, voff_values, (4 * (k - 4) + r) * 1024);
+        constexpr int kAhead = 4 * kRingSets;                      // rows between a refill and its use
+        const int nrow = 4 * k + r + kAhead;                       // compile-time after unrolling
+        if (nrow < 32) ring[k % kRingSets][r] = buf_load16<kAuxStream>(rv_cur, voff_values, nrow * 1024);
+        else           ring[k % kRingSets][r] = buf_load16<kAuxStream>(rv_nxt, voff_values, (nrow - 32) * 1024);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
