@@ -234,9 +234,21 @@ __device__ __forceinline__ void score_steps(const Unit<(RB + TB) / 2>& u, uint32
       c = byte_to_float<K & 3>(rad);
       addr = add_byte<K & 3>(ang, lut_row0);                        // (a << 4) is the entry's byte offset
     } else {
-      const uint32_t sym = symbol<W, K>(u);
-      c = static_cast<float>(sym & ((1u << RB) - 1u));
-      addr = lut_row0 + ((sym >> RB) << 4);
+      // generic widths: bit-field extract per field (after an alignbit if the symbol straddles
+      // two dwords), then v_lshl_add for the table address -- written as instructions because
+      // the compiler otherwise re-associates them into a longer shift/mask/add chain
+      constexpr int bit = K * W, wi = bit >> 5, sh = bit & 31;
+      uint32_t src = u.d[wi];
+      int off = sh;
+      if constexpr (sh + W > 32) {
+        src = __builtin_amdgcn_alignbit(u.d[wi + 1], u.d[wi], sh);
+        off = 0;
+      }
+      uint32_t cq, aq;
+      asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(cq) : "v"(src), "n"(off), "n"(RB));
+      asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(aq) : "v"(src), "n"(off + RB), "n"(TB));
+      asm("v_lshl_add_u32 %0, %1, 4, %2" : "=v"(addr) : "v"(aq), "v"(lut_row0));
+      c = byte_to_float<0>(cq);
     }
     const float rho = fmaf(c, sf[K], zz[K]);
     const Heads<G> t = lut_read<G>(addr + K * ROW);
