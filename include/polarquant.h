@@ -132,6 +132,12 @@ int pq_encode_keys(const pq_layout* layout, const void* keys, pq_dtype key_dtype
  *   out           device fp32 [n_seqs][n_q_heads][d]
  *   scores        optional device fp32 [n_seqs][n_q_heads][scores_stride]: raw q . k~
  *                 (before sm_scale) of tokens < seq_len; NULL to skip (timed runs)
+ *   residual_keys optional device fp16 [n_seqs][n_kv_heads][g][d] (16-byte aligned), see
+ *                 pq_append_keys: when given, the keys of a sequence's last, incomplete group
+ *                 (tokens floor(len/g)*g .. len-1) are read from it un-quantized and scored by
+ *                 plain dot products; packed pages then hold complete groups only.  NULL: the
+ *                 incomplete group, if any, is read from its packed page (as pq_encode_keys
+ *                 writes it).  Values always come from the value pool.
  *   workspace     device, >= pq_decode_workspace_bytes(layout, n_seqs, n_q_heads, max_seq_len),
  *                 256-byte aligned; contents are scratch
  *
@@ -142,7 +148,8 @@ int pq_decode_attention(const pq_layout* layout, const void* q, pq_dtype q_dtype
                         const void* v_pool, int64_t n_pool_pages, const int32_t* block_table,
                         int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
                         float sm_scale, float* out, float* scores, int64_t scores_stride,
-                        void* workspace, size_t workspace_bytes, void* hip_stream);
+                        const void* residual_keys, void* workspace, size_t workspace_bytes,
+                        void* hip_stream);
 
 /*
  * The two stages of pq_decode_attention, callable on their own (the benchmark
@@ -156,11 +163,31 @@ int pq_decode_partials(const pq_layout* layout, const void* q, pq_dtype q_dtype,
                        int32_t n_q_heads, const void* codes_pool, const void* params_pool,
                        const void* v_pool, int64_t n_pool_pages, const int32_t* block_table,
                        int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
-                       float sm_scale, float* scores, int64_t scores_stride, void* workspace,
-                       size_t workspace_bytes, void* hip_stream);
+                       float sm_scale, float* scores, int64_t scores_stride, const void* residual_keys,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
 int pq_decode_merge(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
                     const int32_t* seq_lens, int32_t max_seq_len, float* out,
                     const void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * pq_append_keys -- one decode step's new key per sequence.  Methods of this kind keep the most
+ * recent keys un-quantized until a full group exists (the "residual" of Appendix B.1): the key of
+ * token len (len = seq_lens[s], the length BEFORE the append) is rounded to fp16 and stored in slot
+ * len % g of the sequence's residual buffer; when that completes a group (len % g == g - 1) the g
+ * residual keys are encoded, exactly as pq_encode_keys would encode them, into page
+ * block_table[s][len / g] of the pools.  The caller increments seq_lens afterwards and files the
+ * new value row into the value pool itself.
+ *
+ *   new_keys      device [n_seqs][n_kv_heads][d], post-RoPE, PQ_F16 or PQ_F32 (16-byte aligned)
+ *   residual      device fp16 [n_seqs][n_kv_heads][g][d] (16-byte aligned), owned by the caller
+ *   seq_lens      device int32 [n_seqs]; a negative length skips the sequence
+ *   A group whose page index is >= max_pages_per_seq or whose page id is outside the pool is not
+ *   encoded (nothing is written to the pools).
+ */
+int pq_append_keys(const pq_layout* layout, const void* new_keys, pq_dtype key_dtype, int32_t n_seqs,
+                   void* residual, const int32_t* seq_lens, const int32_t* block_table,
+                   int32_t max_pages_per_seq, void* codes_pool, void* params_pool,
+                   int64_t n_pool_pages, void* hip_stream);
 
 /*
  * pq_score_keys -- the query-key product alone: raw scores q . k~ of every cached token
@@ -168,7 +195,7 @@ int pq_decode_merge(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
  * the paper reports in Section 5.2 (query-key multiplication kernel).  Arguments as in
  * pq_decode_attention; `scores` (device fp32 [n_seqs][n_q_heads][scores_stride], scores_stride
  * >= max_seq_len) receives the scores of tokens < seq_len, other elements are left untouched.
- * No workspace is needed.
+ * No workspace is needed.  Only packed pages are scored (no residual buffer).
  */
 int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
                   int32_t n_q_heads, const void* codes_pool, const void* params_pool,

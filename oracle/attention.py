@@ -18,16 +18,32 @@ import numpy as np
 from . import cache_format, polar
 
 
-def dequant_sequence(codes_pool, params_pool, page_ids, length, r_bits, t_bits, group_tokens):
-    """Reconstructed keys float64 [length, H, d] of one sequence from the packed pools.
+def dequant_sequence(codes_pool, params_pool, page_ids, length, r_bits, t_bits, group_tokens,
+                     residual_seq=None):
+    """Keys float64 [length, H, d] of one sequence as the decode step sees them.
 
     codes_pool uint8 [n_pool_pages, H, P/16, g, 2w]; params_pool fp16 [n_pool_pages, H, P, 2];
-    page_ids: the sequence's pages in order.
+    page_ids: the sequence's pages in order.  Without a residual buffer every token is
+    reconstructed from the packed pages.  With one (fp16 [H, g, d]; Appendix B.1: recent keys
+    stay un-quantized until a full group exists) only the complete groups are, and the keys of
+    the last, incomplete group are the residual rows themselves.
     """
-    n_pages = (length + group_tokens - 1) // group_tokens
-    ids = np.asarray(page_ids[:n_pages], np.int64)
-    a, c, scale, zero = cache_format.unpack_pages(codes_pool[ids], params_pool[ids], length, r_bits, t_bits)
-    return polar.dequant_keys(a, c, scale, zero, t_bits, group_tokens)
+    g = group_tokens
+    if residual_seq is None:
+        n_pages = (length + g - 1) // g
+        ids = np.asarray(page_ids[:n_pages], np.int64)
+        a, c, scale, zero = cache_format.unpack_pages(codes_pool[ids], params_pool[ids], length, r_bits, t_bits)
+        return polar.dequant_keys(a, c, scale, zero, t_bits, g)
+    n_full = length // g
+    rest = length - n_full * g
+    parts = []
+    if n_full:
+        ids = np.asarray(page_ids[:n_full], np.int64)
+        a, c, scale, zero = cache_format.unpack_pages(codes_pool[ids], params_pool[ids], n_full * g, r_bits, t_bits)
+        parts.append(polar.dequant_keys(a, c, scale, zero, t_bits, g))
+    if rest:
+        parts.append(np.asarray(residual_seq)[:, :rest, :].transpose(1, 0, 2).astype(np.float64))
+    return np.concatenate(parts, axis=0)
 
 
 def gather_values(v_pool, page_ids, length, group_tokens):
@@ -55,17 +71,19 @@ def attend(q, k_hat, v, sm_scale):
 
 
 def decode_attention(q, codes_pool, params_pool, v_pool, block_table, seq_lens,
-                     r_bits, t_bits, group_tokens, sm_scale, seqs=None):
+                     r_bits, t_bits, group_tokens, sm_scale, seqs=None, residual=None):
     """One decode step per sequence.
 
     q [S, Hq, d] (any float dtype); pools as in dequant_sequence / gather_values;
-    block_table int [S, max_pages]; seq_lens int [S].  `seqs` restricts the work
-    to some sequences.  Returns {seq: (scores float64 [Hq, L_seq], out float64 [Hq, d])}.
+    block_table int [S, max_pages]; seq_lens int [S]; residual optional fp16 [S, H, g, d].
+    `seqs` restricts the work to some sequences.
+    Returns {seq: (scores float64 [Hq, L_seq], out float64 [Hq, d])}.
     """
     res = {}
     for s in (range(q.shape[0]) if seqs is None else seqs):
         L = int(seq_lens[s])
-        k_hat = dequant_sequence(codes_pool, params_pool, block_table[s], L, r_bits, t_bits, group_tokens)
+        k_hat = dequant_sequence(codes_pool, params_pool, block_table[s], L, r_bits, t_bits, group_tokens,
+                                 None if residual is None else residual[s])
         v = gather_values(v_pool, block_table[s], L, group_tokens)
         res[s] = attend(q[s].astype(np.float64), k_hat, v, sm_scale)
     return res

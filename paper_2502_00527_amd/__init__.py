@@ -21,7 +21,7 @@ __all__ = [
     "Layout", "PQ_F16", "PQ_F32", "PolarQuantError", "lib_path", "load_library",
     "pq_version", "pq_strerror", "pq_codes_bytes_per_page", "pq_params_bytes_per_page",
     "pq_values_bytes_per_page", "pq_decode_workspace_bytes", "pq_encode_keys",
-    "pq_decode_attention", "pq_decode_partials", "pq_decode_merge", "pq_score_keys",
+    "pq_decode_attention", "pq_decode_partials", "pq_decode_merge", "pq_score_keys", "pq_append_keys",
     "pq_probe_read_stream",
 ]
 
@@ -59,10 +59,12 @@ _SIGNATURES = {
                                c_void_p, c_int64, c_void_p]),
     "pq_decode_attention": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                     c_int64, c_void_p, c_int32, c_void_p, c_int32, c_float, c_void_p,
-                                    c_void_p, c_int64, c_void_p, c_size_t, c_void_p]),
+                                    c_void_p, c_int64, c_void_p, c_void_p, c_size_t, c_void_p]),
     "pq_decode_partials": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                    c_int64, c_void_p, c_int32, c_void_p, c_int32, c_float, c_void_p,
-                                   c_int64, c_void_p, c_size_t, c_void_p]),
+                                   c_int64, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "pq_append_keys": (c_int, [_LP, c_void_p, c_int, c_int32, c_void_p, c_void_p, c_void_p, c_int32,
+                               c_void_p, c_void_p, c_int64, c_void_p]),
     "pq_decode_merge": (c_int, [_LP, c_int32, c_int32, c_void_p, c_int32, c_void_p, c_void_p, c_size_t,
                                 c_void_p]),
     "pq_score_keys": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_int64, c_void_p,
@@ -175,7 +177,7 @@ def _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_
 
 
 def pq_decode_attention(layout: Layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens,
-                        max_seq_len: int, sm_scale: float, out, workspace, scores=None) -> None:
+                        max_seq_len: int, sm_scale: float, out, workspace, scores=None, residual=None) -> None:
     """One decode step per sequence; see include/polarquant.h.  `out` fp32 [n_seqs, n_q_heads, d];
     `scores` optional fp32 [n_seqs, n_q_heads, stride >= max_seq_len]; `workspace` a uint8 device
     tensor of at least pq_decode_workspace_bytes(...) bytes."""
@@ -187,12 +189,13 @@ def pq_decode_attention(layout: Layout, q, codes_pool, params_pool, v_pool, bloc
         _dev_ptr(out, "out", (torch.float32,)),
         None if scores is None else _dev_ptr(scores, "scores", (torch.float32,)),
         0 if scores is None else scores.shape[-1],
+        None if residual is None else _dev_ptr(residual, "residual", (torch.float16,)),
         _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream())
     _check(st, "pq_decode_attention")
 
 
 def pq_decode_partials(layout: Layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens,
-                       max_seq_len: int, sm_scale: float, workspace, scores=None) -> None:
+                       max_seq_len: int, sm_scale: float, workspace, scores=None, residual=None) -> None:
     import torch
     c = _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens)
     st = load_library().pq_decode_partials(
@@ -200,6 +203,7 @@ def pq_decode_partials(layout: Layout, q, codes_pool, params_pool, v_pool, block
         c["n_pool"], c["bt"], c["width"], c["lens"], max_seq_len, sm_scale,
         None if scores is None else _dev_ptr(scores, "scores", (torch.float32,)),
         0 if scores is None else scores.shape[-1],
+        None if residual is None else _dev_ptr(residual, "residual", (torch.float16,)),
         _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream())
     _check(st, "pq_decode_partials")
 
@@ -212,6 +216,21 @@ def pq_decode_merge(layout: Layout, n_seqs: int, n_q_heads: int, seq_lens, max_s
         _dev_ptr(out, "out", (torch.float32,)), _dev_ptr(workspace, "workspace"),
         workspace.numel() * workspace.element_size(), _stream())
     _check(st, "pq_decode_merge")
+
+
+def pq_append_keys(layout: Layout, new_keys, residual, seq_lens, block_table, codes_pool, params_pool) -> None:
+    """new_keys [n_seqs, n_kv_heads, d] fp16/fp32; residual fp16 [n_seqs, n_kv_heads, g, d]; seq_lens int32
+    [n_seqs] = lengths before the append (the caller increments them afterwards)."""
+    import torch
+    if new_keys.dim() != 3 or new_keys.shape[1] != layout.n_kv_heads or new_keys.shape[2] != layout.head_dim:
+        raise PolarQuantError("new_keys must be [n_seqs, n_kv_heads, head_dim]")
+    n_pool_pages = codes_pool.numel() * codes_pool.element_size() // max(1, pq_codes_bytes_per_page(layout))
+    st = load_library().pq_append_keys(
+        ctypes.byref(layout), _dev_ptr(new_keys, "new_keys"), _float_kind(new_keys, "new_keys"), new_keys.shape[0],
+        _dev_ptr(residual, "residual", (torch.float16,)), _dev_ptr(seq_lens, "seq_lens", (torch.int32,)),
+        _dev_ptr(block_table, "block_table", (torch.int32,)), block_table.shape[1],
+        _dev_ptr(codes_pool, "codes_pool"), _dev_ptr(params_pool, "params_pool"), n_pool_pages, _stream())
+    _check(st, "pq_append_keys")
 
 
 def pq_score_keys(layout: Layout, q, codes_pool, params_pool, block_table, seq_lens, max_seq_len: int,

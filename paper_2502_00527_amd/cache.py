@@ -37,12 +37,13 @@ class DeviceCache:
     def sm_scale(self) -> float:
         return 1.0 / float(np.sqrt(self.wl.head_dim))
 
-    def decode(self, out: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None):
+    def decode(self, out: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
+               residual: Optional[torch.Tensor] = None):
         if out is None:
             out = torch.empty((self.wl.n_seqs, self.wl.n_q_heads, self.wl.head_dim), dtype=torch.float32,
                               device=self.q.device)
         pq_decode_attention(self.layout, self.q, self.codes, self.params, self.values, self.block_table,
-                            self.seq_lens, self.max_seq_len, self.sm_scale, out, self.workspace, scores)
+                            self.seq_lens, self.max_seq_len, self.sm_scale, out, self.workspace, scores, residual)
         return out
 
 

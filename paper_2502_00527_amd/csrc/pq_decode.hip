@@ -46,6 +46,7 @@ struct DecodeArgs {
   const uint8_t* codes;
   const uint32_t* params;   // {fp16 s, fp16 z} per pair, viewed as one dword
   const __half* values;
+  const __half* residual;   // [seq][kv_head][g][d] un-quantized keys of the last, incomplete group (or null)
   const int32_t* block_table;
   const int32_t* seq_lens;
   float* scores;
@@ -93,6 +94,20 @@ __device__ __forceinline__ float row_sum(float x) {
   x += __shfl_xor(x, 2);
   return x + __shfl_xor(x, 1);
 }
+// Sum of the four 16-lane rows' partial scores: with 4 query heads row h ends with head h's
+// score (transposing fold), with 2 heads rows 0-1 / 2-3, with 1 head every row.
+template <int G>
+__device__ __forceinline__ float fold_rows(const float (&part)[G]) {
+  if constexpr (G == 4) {
+    return tsum16(tsum32(part[0], part[2]), tsum32(part[1], part[3]));
+  } else if constexpr (G == 2) {
+    const float b = tsum32(part[0], part[1]);
+    return tsum16(b, b);
+  } else {
+    return sum_rows(part[0]);
+  }
+}
+
 // LDS written by some lanes of this wavefront is about to be read by others.
 __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -258,6 +273,33 @@ __device__ __forceinline__ void score_steps(const Unit<(RB + TB) / 2>& u, uint32
   }
 }
 
+// Residual keys (the un-quantized tail of a sequence): part[h] += sum over this lane's 32 dims
+// (pairs 16*row .. 16*row+15, i.e. dims 16*row.. and 64+16*row..) of k[dim] * q_h[dim].
+// kx / ky are the 16 fp16 x- and y-coordinates of the lane's pairs; `qs_row` is the LDS byte
+// address of q[dim = 16*row][heads], 16 bytes per dim.
+template <int G>
+__device__ __forceinline__ void dense_steps(const uint4 (&kx)[2], const uint4 (&ky)[2], uint32_t qs_row,
+                                            float (&part)[G]) {
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const uint4(&kk)[2] = half == 0 ? kx : ky;
+#pragma unroll
+    for (int v = 0; v < 2; ++v) {
+      const uint32_t w4[4] = {kk[v].x, kk[v].y, kk[v].z, kk[v].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const __half2 hv = *reinterpret_cast<const __half2*>(&w4[e]);
+        const float k0 = __low2float(hv), k1 = __high2float(hv);
+        const int dim = half * kPairs + v * 8 + 2 * e;            // relative to 16 * row
+        const Heads<G> q0 = lut_read<G>(qs_row + dim * 16);
+        const Heads<G> q1 = lut_read<G>(qs_row + (dim + 1) * 16);
+#pragma unroll
+        for (int h = 0; h < G; ++h) part[h] = fmaf(k1, q1.v[h], fmaf(k0, q0.v[h], part[h]));
+      }
+    }
+  }
+}
+
 // acc[h][0..7] += p_h[token] * V[token][this lane's 8 dims] for the 4 value rows in `vv`
 // (tokens 4 * (it0 + i) + row); pw is prob[token][G] in LDS.
 template <int G>
@@ -293,6 +335,8 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   __shared__ __attribute__((aligned(16))) float alpha_s[kWaves][4];
   __shared__ __attribute__((aligned(16))) float red_acc[kWaves][G][kHeadDim];
   __shared__ float red_ml[kWaves][G][2];
+  __shared__ __attribute__((aligned(16))) float q_lds[kHeadDim][4];   // q[dim][head] for residual keys
+  __shared__ float res_sc[kGroup * G];                                // raw scores of the residual group
 
   // Chunk-major launch order: the KV heads of one page are neighbours in memory and run
   // together; every sequence's first chunks run first, and the chunks that only long sequences
@@ -337,6 +381,8 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
     if (pid >= 0 && pid < a.n_pool_pages) pid_lane = static_cast<int>(pid);
   }
   constexpr uint32_t kCodesBytes = kBlocks * kGroup * UB;          // codes of one (page, kv head)
+  // With a residual buffer the last, incomplete group of the sequence is kept as fp16 keys.
+  const int res_page = (a.residual != nullptr && (L % kGroup) != 0) ? L / kGroup : -1;
   // Buffer descriptors of the wavefront's k-th page; a masked page gets empty descriptors
   // (every read returns zero) and zero valid tokens.
   auto page_setup = [&](int k, __amdgpu_buffer_rsrc_t& rc, __amdgpu_buffer_rsrc_t& rp,
@@ -345,8 +391,9 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
     const bool ok = pid >= 0;
     const int64_t ph = ok ? static_cast<int64_t>(pid) * a.n_kv_heads + kvh : 0;
     nv = ok ? min(kGroup, L - (page0 + wave + kWaves * k) * kGroup) : 0;
-    rc = make_rsrc(a.codes + ph * kCodesBytes, ok ? kCodesBytes : 0u);
-    rp = make_rsrc(a.params + ph * kPairs, ok ? kPairs * 4u : 0u);
+    const bool packed = ok && (page0 + wave + kWaves * k) != res_page;   // the residual group has no codes yet
+    rc = make_rsrc(a.codes + ph * kCodesBytes, packed ? kCodesBytes : 0u);
+    rp = make_rsrc(a.params + ph * kPairs, packed ? kPairs * 4u : 0u);
     rv = make_rsrc(a.values + ph * (kGroup * kHeadDim), static_cast<uint32_t>(nv) * (kHeadDim * 2));
   };
 
@@ -395,8 +442,41 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
         lf[idx * 4 + h] = fmaf(qx, cs, qy * sn);
       }
     }
+    if (tid < kHeadDim) {
+#pragma unroll
+      for (int h = 0; h < G; ++h) q_lds[tid][h] = static_cast<float>(qb[h * kHeadDim + tid]);
+    }
   }
   __syncthreads();
+
+  // ---- residual group (at most one per sequence): scored here, before the page loop, by the
+  // wavefront that owns its page -- plain dot products with the fp16 keys in the same lane
+  // layout (each lane takes the 32 dims of its 16 pairs) and with the same fold; key rows past
+  // the sequence end read as zero.  The loop below picks the scores up from LDS.
+  if (res_page >= page0 + wave && res_page < page0 + npg && ((res_page - page0 - wave) & (kWaves - 1)) == 0) {
+    const int nv_res = L - res_page * kGroup;
+    const __amdgpu_buffer_rsrc_t rs_res = make_rsrc(
+        a.residual + (static_cast<int64_t>(seq) * a.n_kv_heads + kvh) * (kGroup * kHeadDim),
+        static_cast<uint32_t>(nv_res) * (kHeadDim * 2));
+    const uint32_t voff_res = col * (kHeadDim * 2) + row * 32;
+    const uint32_t qs_row = lds_addr(q_lds) + row * (16 * 16);
+#pragma unroll 1
+    for (int s = 0; s < 8; ++s) {
+      uint4 kx[2], ky[2];
+      const uint32_t soff = s * 16 * kHeadDim * 2;
+      kx[0] = buf_load16<kAuxCached>(rs_res, voff_res, soff);
+      kx[1] = buf_load16<kAuxCached>(rs_res, voff_res + 16, soff);
+      ky[0] = buf_load16<kAuxCached>(rs_res, voff_res + kPairs * 2, soff);
+      ky[1] = buf_load16<kAuxCached>(rs_res, voff_res + kPairs * 2 + 16, soff);
+      float part[G];
+#pragma unroll
+      for (int h = 0; h < G; ++h) part[h] = 0.f;
+      dense_steps<G>(kx, ky, qs_row, part);
+      const float v = fold_rows<G>(part);
+      if (owner) res_sc[(s * 16 + col) * G + my_head] = v;
+    }
+    wave_lds_sync();
+  }
 
   for (int i = 0; i < n_w; ++i) {
     const int pi = page0 + wave + kWaves * i;                      // chunk-relative page of iteration i
@@ -423,20 +503,20 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
 
     // ---- scores of the page's 128 tokens: 8 passes of 16 tokens ----
     float sc[8];
+    if (pi != res_page) {
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      float part[G];
+      for (int s = 0; s < 8; ++s) {
+        float part[G];
 #pragma unroll
-      for (int h = 0; h < G; ++h) part[h] = 0.f;
-      score_steps<G, RB, TB, 0>(cu[s], lut_row0, sf, zz, part);
-      if constexpr (G == 4) {
-        sc[s] = tsum16(tsum32(part[0], part[2]), tsum32(part[1], part[3]));
-      } else if constexpr (G == 2) {
-        const float b = tsum32(part[0], part[1]);
-        sc[s] = tsum16(b, b);
-      } else {
-        sc[s] = sum_rows(part[0]);
+        for (int h = 0; h < G; ++h) part[h] = 0.f;
+        score_steps<G, RB, TB, 0>(cu[s], lut_row0, sf, zz, part);
+        sc[s] = fold_rows<G>(part);
       }
+    } else {
+      // residual group: its scores were computed before the loop (plain dot products)
+#pragma unroll
+      for (int s = 0; s < 8; ++s)
+        sc[s] = *(const PQ_LDS float*)static_cast<uintptr_t>(lds_addr(res_sc) + ((s * 16 + col) * G + my_head) * 4);
     }
 
     // ---- online softmax over the page (log2 domain) ----
@@ -807,8 +887,9 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
                                   int32_t n_q_heads, const void* codes_pool, const void* params_pool,
                                   const void* v_pool, int64_t n_pool_pages, const int32_t* block_table,
                                   int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
-                                  float sm_scale, float* scores, int64_t scores_stride, void* workspace,
-                                  size_t workspace_bytes, void* hip_stream) {
+                                  float sm_scale, float* scores, int64_t scores_stride,
+                                  const void* residual_keys, void* workspace, size_t workspace_bytes,
+                                  void* hip_stream) {
   const int st = check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len);
   if (st != PQ_OK) return st;
   if (!q || !codes_pool || !params_pool || !v_pool || !block_table || !seq_lens) return PQ_ERR_INVALID_ARG;
@@ -818,6 +899,7 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
   if (need_pages > max_pages_per_seq) return PQ_ERR_INVALID_ARG;
   if (scores && scores_stride < max_seq_len) return PQ_ERR_INVALID_ARG;
   if (!isfinite(sm_scale)) return PQ_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(residual_keys) & 15u) return PQ_ERR_INVALID_ARG;
 
   const ChunkPlan plan = plan_chunks(n_seqs, layout->n_kv_heads, max_seq_len);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return PQ_ERR_WORKSPACE;
@@ -829,6 +911,7 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
   a.codes = static_cast<const uint8_t*>(codes_pool);
   a.params = static_cast<const uint32_t*>(params_pool);
   a.values = static_cast<const __half*>(v_pool);
+  a.residual = static_cast<const __half*>(residual_keys);
   a.block_table = block_table;
   a.seq_lens = seq_lens;
   a.scores = scores;
@@ -886,11 +969,13 @@ extern "C" int pq_decode_attention(const pq_layout* layout, const void* q, pq_dt
                                    const void* v_pool, int64_t n_pool_pages, const int32_t* block_table,
                                    int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
                                    float sm_scale, float* out, float* scores, int64_t scores_stride,
-                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
+                                   const void* residual_keys, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream) {
   if (!out) return PQ_ERR_INVALID_ARG;
   const int st = pq_decode_partials(layout, q, q_dtype, n_seqs, n_q_heads, codes_pool, params_pool, v_pool,
                                     n_pool_pages, block_table, max_pages_per_seq, seq_lens, max_seq_len,
-                                    sm_scale, scores, scores_stride, workspace, workspace_bytes, hip_stream);
+                                    sm_scale, scores, scores_stride, residual_keys, workspace, workspace_bytes,
+                                    hip_stream);
   if (st != PQ_OK) return st;
   return pq_decode_merge(layout, n_seqs, n_q_heads, seq_lens, max_seq_len, out, workspace, workspace_bytes,
                          hip_stream);

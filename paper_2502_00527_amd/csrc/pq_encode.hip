@@ -88,19 +88,16 @@ __device__ __forceinline__ float max_nonneg(float p, float q) {
   return __uint_as_float(max(__float_as_uint(p), __float_as_uint(q)));
 }
 
+// Encodes one group (page) of one KV head with the 256 threads of the calling work-group.
+// `keys` points at the head's d elements of the group's first token; rows are token_stride
+// elements apart; nv <= 128 tokens are valid.  codes_ph / params_ph are the (page, head) slices
+// of the pools.  Contains a work-group barrier: all threads must call it.
 template <int RB, int TB, typename KT>
-__global__ __launch_bounds__(kEncThreads) void pq_encode_kernel(const EncodeArgs a) {
+__device__ __forceinline__ void encode_group(const KT* keys, int64_t token_stride, int nv, uint8_t* codes_ph,
+                                             uint32_t* params_ph, const double* tan_edge,
+                                             float (*s_mn)[kPairs], float (*s_mx)[kPairs]) {
   constexpr int W = RB + TB;
   constexpr int UB = 2 * W;
-  __shared__ float s_mn[kEncThreads / 64][kPairs];
-  __shared__ float s_mx[kEncThreads / 64][kPairs];
-
-  const int grp = blockIdx.x, kvh = blockIdx.y;
-  const int64_t page = a.page_ids[grp];
-  if (page < 0 || page >= a.n_pool_pages) return;
-  const int64_t tok0 = static_cast<int64_t>(grp) * kGroup;
-  const int nv = static_cast<int>(min<int64_t>(kGroup, a.n_tokens - tok0));
-
   const int tid = threadIdx.x;
   const int o = tid & 7;          // pairs 8o .. 8o+7
   const int slot = tid >> 3;      // tokens slot, slot+32, slot+64, slot+96
@@ -112,14 +109,14 @@ __global__ __launch_bounds__(kEncThreads) void pq_encode_kernel(const EncodeArgs
 #pragma unroll
   for (int e = 0; e < 8; ++e) { mn[e] = INFINITY; mx[e] = 0.f; }
 
-  const KT* base = static_cast<const KT*>(a.keys) + kvh * a.head_stride + o * 8;
+  const KT* base = keys + o * 8;
 #pragma unroll
   for (int it = 0; it < kItems; ++it) {
     const int tok = slot + 32 * it;
     ang[it][0] = ang[it][1] = 0u;
     if (tok < nv) {
       float x[8], y[8];
-      const KT* p = base + (tok0 + tok) * a.token_stride;
+      const KT* p = base + tok * token_stride;
       load8(p, x);
       load8(p + kPairs, y);
 #pragma unroll
@@ -130,7 +127,7 @@ __global__ __launch_bounds__(kEncThreads) void pq_encode_kernel(const EncodeArgs
         rho[it][e] = r;
         mn[e] = min_nonneg(mn[e], r);
         mx[e] = max_nonneg(mx[e], r);
-        ang[it][e >> 2] |= angle_bin<TB>(x[e], y[e], a.tan_edge) << (8 * (e & 3));
+        ang[it][e >> 2] |= angle_bin<TB>(x[e], y[e], tan_edge) << (8 * (e & 3));
       }
     } else {
 #pragma unroll
@@ -174,13 +171,13 @@ __global__ __launch_bounds__(kEncThreads) void pq_encode_kernel(const EncodeArgs
                        (static_cast<uint32_t>(__half_as_ushort(zh)) << 16);
   }
   if (slot == 0) {
-    uint4* dst = reinterpret_cast<uint4*>(a.params + (page * a.n_kv_heads + kvh) * kPairs + o * 8);
+    uint4* dst = reinterpret_cast<uint4*>(params_ph + o * 8);
     dst[0] = make_uint4(packed_params[0], packed_params[1], packed_params[2], packed_params[3]);
     dst[1] = make_uint4(packed_params[4], packed_params[5], packed_params[6], packed_params[7]);
   }
 
   // radius codes, symbols, and the bit string of this thread's 8 pairs (8*W bits)
-  uint8_t* const cbase = a.codes + ((page * a.n_kv_heads + kvh) * kBlocks + (o >> 1)) * kGroup * UB;
+  uint8_t* const cbase = codes_ph + (o >> 1) * kGroup * UB;
 #pragma unroll
   for (int it = 0; it < kItems; ++it) {
     const int tok = slot + 32 * it;
@@ -212,6 +209,67 @@ __global__ __launch_bounds__(kEncThreads) void pq_encode_kernel(const EncodeArgs
       }
     }
   }
+}
+
+template <int RB, int TB, typename KT>
+__global__ __launch_bounds__(kEncThreads) void pq_encode_kernel(const EncodeArgs a) {
+  __shared__ float s_mn[kEncThreads / 64][kPairs];
+  __shared__ float s_mx[kEncThreads / 64][kPairs];
+  const int grp = blockIdx.x, kvh = blockIdx.y;
+  const int64_t page = a.page_ids[grp];
+  if (page < 0 || page >= a.n_pool_pages) return;
+  const int64_t tok0 = static_cast<int64_t>(grp) * kGroup;
+  const int nv = static_cast<int>(min<int64_t>(kGroup, a.n_tokens - tok0));
+  const int64_t ph = page * a.n_kv_heads + kvh;
+  encode_group<RB, TB, KT>(static_cast<const KT*>(a.keys) + tok0 * a.token_stride + kvh * a.head_stride,
+                           a.token_stride, nv, a.codes + ph * (kBlocks * kGroup * 2 * (RB + TB)),
+                           a.params + ph * kPairs, a.tan_edge, s_mn, s_mx);
+}
+
+// Appends one decode step's key per sequence to the fp16 residual buffer and, when that fills a
+// group of 128 tokens, encodes the group into its page (the residual mechanism the paper's
+// Appendix B.1 refers to: recent keys stay un-quantized until a full group exists).
+struct AppendArgs {
+  const void* new_keys;        // [seq][kv_head][d]
+  __half* residual;            // [seq][kv_head][g][d]
+  const int32_t* seq_lens;     // lengths BEFORE the append
+  const int32_t* block_table;
+  uint8_t* codes;
+  uint32_t* params;
+  int64_t n_pool_pages;
+  int32_t n_kv_heads;
+  int32_t max_pages_per_seq;
+  double tan_edge[kMaxAngleBins / 8];
+};
+
+template <int RB, int TB, typename KT>
+__global__ __launch_bounds__(kEncThreads) void pq_append_kernel(const AppendArgs a) {
+  __shared__ float s_mn[kEncThreads / 64][kPairs];
+  __shared__ float s_mx[kEncThreads / 64][kPairs];
+  const int kvh = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x;
+  const int L = a.seq_lens[seq];
+  if (L < 0) return;
+  const int slot = L % kGroup, grp = L / kGroup;
+  const int64_t sh = static_cast<int64_t>(seq) * a.n_kv_heads + kvh;
+  __half* const res = a.residual + sh * (kGroup * kHeadDim);
+  if (tid < kHeadDim / 8) {
+    float v[8];
+    load8(static_cast<const KT*>(a.new_keys) + sh * kHeadDim + tid * 8, v);
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      w[e] = static_cast<uint32_t>(__half_as_ushort(__float2half_rn(v[2 * e]))) |
+             (static_cast<uint32_t>(__half_as_ushort(__float2half_rn(v[2 * e + 1]))) << 16);
+    *reinterpret_cast<uint4*>(res + slot * kHeadDim + tid * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  if (slot != kGroup - 1) return;                 // the group is not complete yet (uniform)
+  if (grp >= a.max_pages_per_seq) return;
+  const int64_t page = a.block_table[static_cast<int64_t>(seq) * a.max_pages_per_seq + grp];
+  if (page < 0 || page >= a.n_pool_pages) return;
+  __syncthreads();                                // the new row is visible to the whole work-group
+  const int64_t ph = page * a.n_kv_heads + kvh;
+  encode_group<RB, TB, __half>(res, kHeadDim, kGroup, a.codes + ph * (kBlocks * kGroup * 2 * (RB + TB)),
+                               a.params + ph * kPairs, a.tan_edge, s_mn, s_mx);
 }
 
 template <int RB, int TB>
@@ -270,6 +328,60 @@ extern "C" int pq_encode_keys(const pq_layout* layout, const void* keys, pq_dtyp
     case 35: e = launch_encode<3, 5>(a, key_dtype, grid, st); break;
     case 42: e = launch_encode<4, 2>(a, key_dtype, grid, st); break;
     case 24: e = launch_encode<2, 4>(a, key_dtype, grid, st); break;
+    default: return PQ_ERR_UNSUPPORTED;
+  }
+  if (e != hipSuccess) return record_hip_error(e);
+  return PQ_OK;
+}
+
+namespace pq {
+namespace {
+template <int RB, int TB>
+hipError_t launch_append(const AppendArgs& a, pq_dtype dt, dim3 grid, hipStream_t st) {
+  if (dt == PQ_F16) hipLaunchKernelGGL((pq_append_kernel<RB, TB, __half>), grid, dim3(kEncThreads), 0, st, a);
+  else              hipLaunchKernelGGL((pq_append_kernel<RB, TB, float>), grid, dim3(kEncThreads), 0, st, a);
+  return hipGetLastError();
+}
+}  // namespace
+}  // namespace pq
+
+extern "C" int pq_append_keys(const pq_layout* layout, const void* new_keys, pq_dtype key_dtype, int32_t n_seqs,
+                              void* residual, const int32_t* seq_lens, const int32_t* block_table,
+                              int32_t max_pages_per_seq, void* codes_pool, void* params_pool,
+                              int64_t n_pool_pages, void* hip_stream) {
+  if (!layout) return PQ_ERR_INVALID_ARG;
+  if (!layout_supported(layout)) return PQ_ERR_UNSUPPORTED;
+  if (n_seqs < 0 || n_pool_pages <= 0 || max_pages_per_seq <= 0) return PQ_ERR_INVALID_ARG;
+  if (key_dtype != PQ_F16 && key_dtype != PQ_F32) return PQ_ERR_INVALID_ARG;
+  if (n_seqs == 0) return PQ_OK;
+  if (!new_keys || !residual || !seq_lens || !block_table || !codes_pool || !params_pool) return PQ_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(new_keys) & 15u) || (reinterpret_cast<uintptr_t>(residual) & 15u) ||
+      (reinterpret_cast<uintptr_t>(codes_pool) & 15u) || (reinterpret_cast<uintptr_t>(params_pool) & 15u))
+    return PQ_ERR_INVALID_ARG;
+  if (n_seqs > 65535) return PQ_ERR_UNSUPPORTED;
+  AppendArgs a;
+  a.new_keys = new_keys;
+  a.residual = static_cast<__half*>(residual);
+  a.seq_lens = seq_lens;
+  a.block_table = block_table;
+  a.codes = static_cast<uint8_t*>(codes_pool);
+  a.params = static_cast<uint32_t*>(params_pool);
+  a.n_pool_pages = n_pool_pages;
+  a.n_kv_heads = layout->n_kv_heads;
+  a.max_pages_per_seq = max_pages_per_seq;
+  const int nb = 1 << layout->t_bits;
+  for (int k = 0; k < kMaxAngleBins / 8; ++k)
+    a.tan_edge[k] = (k >= 1 && k < nb / 8) ? tan(k * (2.0 * M_PI / nb)) : 0.0;
+  const dim3 grid(layout->n_kv_heads, n_seqs);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = hipSuccess;
+  switch (layout->r_bits * 10 + layout->t_bits) {
+    case 44: e = launch_append<4, 4>(a, key_dtype, grid, st); break;
+    case 33: e = launch_append<3, 3>(a, key_dtype, grid, st); break;
+    case 53: e = launch_append<5, 3>(a, key_dtype, grid, st); break;
+    case 35: e = launch_append<3, 5>(a, key_dtype, grid, st); break;
+    case 42: e = launch_append<4, 2>(a, key_dtype, grid, st); break;
+    case 24: e = launch_append<2, 4>(a, key_dtype, grid, st); break;
     default: return PQ_ERR_UNSUPPORTED;
   }
   if (e != hipSuccess) return record_hip_error(e);

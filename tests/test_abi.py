@@ -69,14 +69,16 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     bad = pq.Layout(128, 7, 1, 128, 8)
     assert lib.pq_encode_keys(ctypes.byref(bad), null, 0, 1024, 128, 10, null, null, null, 4, null) == -2
     st = lib.pq_decode_attention(ctypes.byref(lay), null, 0, 1, 32, null, null, null, 4, null, 1, null, 128,
-                                 0.1, null, null, 0, null, 0, null)
+                                 0.1, null, null, 0, null, null, 0, null)
     assert st == -1
     fake = ctypes.c_void_p(4096)
     st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 4, fake, 1, fake, 128,
-                                0.1, null, 0, null, 0, null)
+                                0.1, null, 0, null, null, 0, null)
     assert st == -3 and "workspace" in pq.pq_strerror(st)
     # more pages needed than the block table is wide
     st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 4, fake, 1, fake, 129,
-                                0.1, null, 0, fake, 1 << 20, null)
+                                0.1, null, 0, null, fake, 1 << 20, null)
+    assert st == -1
+    st = lib.pq_append_keys(ctypes.byref(lay), null, 0, 4, null, null, null, 8, null, null, 16, null)
     assert st == -1
     assert pq.pq_version() >= 100

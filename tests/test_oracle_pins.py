@@ -378,3 +378,52 @@ def test_paged_decode_equals_contiguous():
     for s in range(3):
         np.testing.assert_allclose(got[s][0], want[s][0], atol=1e-12)
         np.testing.assert_allclose(got[s][1], want[s][1], atol=1e-12)
+
+
+# --------------------------------------------------------------------------- residual keys
+
+def test_residual_keys_are_scored_unquantized():
+    """With a residual buffer the incomplete last group is plain fp16 keys (Appendix B.1): a
+    sequence shorter than one group is textbook attention on the fp16 keys, and in a longer one
+    only the complete groups are reconstructed from codes."""
+    rng = np.random.default_rng(11)
+    g, H, Hq, d, r, t = 128, 2, 4, 128, 4, 4
+    L = 300
+    keys = rng.standard_normal((L, H, d)).astype(np.float16)
+    vals = rng.standard_normal((L, H, d)).astype(np.float16)
+    q = rng.standard_normal((1, Hq, d))
+    n_full = L // g
+    enc = polar.encode_keys(keys[: n_full * g], r, t, g)
+    codes, params = cache_format.pack_sequence(enc["a"], enc["c"], enc["scale"], enc["zero"], r, t, g)
+    n_pages = n_full + 1
+    codes_pool = np.concatenate([codes, np.full((1,) + codes.shape[1:], 0xEE, np.uint8)])      # junk page
+    params_pool = np.concatenate([params, np.full((1,) + params.shape[1:], np.nan, np.float16)])
+    v = np.zeros((n_pages * g, H, d), np.float16)
+    v[:L] = vals
+    v_pool = v.reshape(n_pages, g, H, d).transpose(0, 2, 1, 3)
+    residual = np.full((1, H, g, d), np.nan, np.float16)
+    residual[0, :, : L - n_full * g] = keys[n_full * g:].transpose(1, 0, 2)
+    table = np.arange(n_pages)[None, :]
+    res = attention.decode_attention(q, codes_pool, params_pool, v_pool, table, [L], r, t, g, 0.09,
+                                     residual=residual)[0]
+    k_hat = polar.dequant_keys(enc["a"], enc["c"], enc["scale"], enc["zero"], t, g)
+    k_all = np.concatenate([k_hat, keys[n_full * g:].astype(np.float64)])
+    want = attention.attend(q[0], k_all, vals.astype(np.float64), 0.09)
+    np.testing.assert_allclose(res[0], want[0], atol=1e-12)
+    np.testing.assert_allclose(res[1], want[1], atol=1e-12)
+    # the tail scores are exact dot products with the fp16 keys
+    exact = np.einsum("hd,ld->hl", q[0][:2], keys[n_full * g:, 0, :].astype(np.float64))
+    np.testing.assert_allclose(res[0][:2, n_full * g:], exact, atol=1e-12)
+    # shorter than a group: textbook attention (torch float64) on the fp16 keys
+    Ls = 77
+    resid2 = np.full((1, H, g, d), np.nan, np.float16)
+    resid2[0, :, :Ls] = keys[:Ls].transpose(1, 0, 2)
+    v2 = np.zeros((g, H, d), np.float16)
+    v2[:Ls] = vals[:Ls]
+    out2 = attention.decode_attention(q, codes_pool[-1:], params_pool[-1:], v2.reshape(1, g, H, d).transpose(0, 2, 1, 3),
+                                      np.zeros((1, 1), int), [Ls], r, t, g, 1 / math.sqrt(d), residual=resid2)[0][1]
+    tq = torch.from_numpy(q[0])[None, :, None, :]
+    tk = torch.from_numpy(keys[:Ls].astype(np.float64)).permute(1, 0, 2).repeat_interleave(2, 0)[None]
+    tv = torch.from_numpy(vals[:Ls].astype(np.float64)).permute(1, 0, 2).repeat_interleave(2, 0)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv)[0, :, 0, :].numpy()
+    np.testing.assert_allclose(out2, ref, atol=1e-12)
