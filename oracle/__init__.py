@@ -10,6 +10,7 @@ never does, and this package imports nothing from the product.
 Modules
   polar.py         pair -> (radius, angle) -> group-wise codes; mid-point dequantizer
   cache_format.py  the packed page layout (an independent write-up of the byte format)
+  values.py        token-wise value quantizer (the paper's optional value quantization)
   attention.py     dequantize-then-dot scores, softmax, fp16-V aggregation over a paged cache
 
 Every function is pinned by the CPU tests (closed forms, hand-worked values

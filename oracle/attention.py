@@ -15,7 +15,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import cache_format, polar
+from . import cache_format, polar, values
 
 
 def dequant_sequence(codes_pool, params_pool, page_ids, length, r_bits, t_bits, group_tokens,
@@ -54,6 +54,19 @@ def gather_values(v_pool, page_ids, length, group_tokens):
     return v.reshape(n_pages * group_tokens, v.shape[2], v.shape[3])[:length].astype(np.float64)
 
 
+def gather_quantized_values(vq_pool, vq_params, page_ids, length, group_tokens, bits):
+    """Dequantized values float64 [length, H, d] of one sequence.
+
+    vq_pool uint8 [n_pool_pages, H, g/T, d/8, 16]; vq_params fp16 [n_pool_pages, H, g, 2] = (scale, zero).
+    """
+    g = group_tokens
+    n_pages = (length + g - 1) // g
+    ids = np.asarray(page_ids[:n_pages], np.int64)
+    codes = cache_format.unpack_value_pages(vq_pool[ids], length, bits)               # [L, H, d]
+    par = vq_params[ids].transpose(0, 2, 1, 3).reshape(n_pages * g, vq_params.shape[1], 2)[:length]
+    return values.dequant_values(codes, par[..., 0], par[..., 1])
+
+
 def attend(q, k_hat, v, sm_scale):
     """q float64 [Hq, d]; k_hat, v float64 [L, Hkv, d] -> (scores [Hq, L], out [Hq, d])."""
     n_q, n_kv = q.shape[0], k_hat.shape[1]
@@ -71,11 +84,13 @@ def attend(q, k_hat, v, sm_scale):
 
 
 def decode_attention(q, codes_pool, params_pool, v_pool, block_table, seq_lens,
-                     r_bits, t_bits, group_tokens, sm_scale, seqs=None, residual=None):
+                     r_bits, t_bits, group_tokens, sm_scale, seqs=None, residual=None,
+                     vq_params=None, v_bits=16):
     """One decode step per sequence.
 
     q [S, Hq, d] (any float dtype); pools as in dequant_sequence / gather_values;
     block_table int [S, max_pages]; seq_lens int [S]; residual optional fp16 [S, H, g, d].
+    With v_bits 4 or 2, v_pool holds quantized value pages and vq_params their (scale, zero).
     `seqs` restricts the work to some sequences.
     Returns {seq: (scores float64 [Hq, L_seq], out float64 [Hq, d])}.
     """
@@ -84,6 +99,9 @@ def decode_attention(q, codes_pool, params_pool, v_pool, block_table, seq_lens,
         L = int(seq_lens[s])
         k_hat = dequant_sequence(codes_pool, params_pool, block_table[s], L, r_bits, t_bits, group_tokens,
                                  None if residual is None else residual[s])
-        v = gather_values(v_pool, block_table[s], L, group_tokens)
+        if v_bits == 16:
+            v = gather_values(v_pool, block_table[s], L, group_tokens)
+        else:
+            v = gather_quantized_values(v_pool, vq_params, block_table[s], L, group_tokens, v_bits)
         res[s] = attend(q[s].astype(np.float64), k_hat, v, sm_scale)
     return res

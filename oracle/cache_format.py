@@ -16,6 +16,13 @@ its public header and the two write-ups share no code.
 
 A page holds `g` tokens (one quantization group).  Slots of a partial last
 page beyond the sequence length hold zero bytes.
+
+Quantized values (optional, b = 4 or 2 bits per element, token-wise parameters):
+  value unit  = 16 bytes = T = 16 / b consecutive tokens x 8 consecutive dims:
+                token i of the unit is the b*8-bit field [i*8*b, (i+1)*8*b) of the unit (little
+                endian), and dim k of that token is the b-bit field k of it
+  vq page     = [kv_head][token block = token // T][dim slice = dim // 8][unit]
+  vq params   = [kv_head][token]{fp16 scale, fp16 zero}
 """
 from __future__ import annotations
 
@@ -91,3 +98,34 @@ def codes_bytes_per_page(n_kv_heads: int, head_dim: int, r_bits: int, t_bits: in
 
 def params_bytes_per_page(n_kv_heads: int, head_dim: int) -> int:
     return n_kv_heads * (head_dim // 2) * 2 * 2
+
+
+def pack_value_page_stream(codes: np.ndarray, bits: int, group_tokens: int) -> np.ndarray:
+    """Quantized value codes of one sequence -> pages.
+
+    codes int [L, H, d] (b-bit each) -> uint8 [n_pages, H, g / T, d / 8, 16], T = 16 / bits tokens
+    per unit; slots past the sequence end are zero.
+    """
+    L, H, d = codes.shape
+    g = group_tokens
+    T = 16 // bits
+    n_pages = (L + g - 1) // g
+    full = np.zeros((n_pages * g, H, d), np.int64)
+    full[:L] = codes
+    assert full.min() >= 0 and full.max() < (1 << bits)
+    # [page, token block, token in unit, H, dim slice, dim in slice]
+    x = full.reshape(n_pages, g // T, T, H, d // 8, 8)
+    x = x.transpose(0, 3, 1, 4, 2, 5)                                       # [page, H, block, slice, T, 8]
+    bit_planes = ((x[..., None] >> np.arange(bits)) & 1).astype(np.uint8)     # LSB first per element
+    stream = bit_planes.reshape(n_pages, H, g // T, d // 8, T * 8 * bits)     # token-major, dim, bit
+    return np.packbits(stream, axis=-1, bitorder="little")
+
+
+def unpack_value_pages(pages: np.ndarray, length: int, bits: int) -> np.ndarray:
+    """Inverse of pack_value_page_stream: uint8 [n_pages, H, g/T, d/8, 16] -> int64 [length, H, d]."""
+    n_pages, H, n_blocks, n_slices, _ = pages.shape
+    T = 16 // bits
+    b = np.unpackbits(pages, axis=-1, bitorder="little").reshape(n_pages, H, n_blocks, n_slices, T, 8, bits)
+    x = (b.astype(np.int64) << np.arange(bits)).sum(axis=-1)                # [page, H, block, slice, T, 8]
+    x = x.transpose(0, 2, 4, 1, 3, 5).reshape(n_pages * n_blocks * T, H, n_slices * 8)
+    return x[:length]
