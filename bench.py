@@ -28,11 +28,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 
 
-def algorithmic_bytes(wl, lens) -> int:
-    """Bytes the method must move per launch: codes + radius params + fp16 values of every
-    cached (KV head, token)."""
+def algorithmic_bytes(wl, lens, v_bits: int = 16) -> int:
+    """Bytes the method must move per launch: codes + radius params + values (fp16, or b-bit codes
+    plus 4 bytes of scale / zero-point per token) of every cached (KV head, token)."""
     w = wl.r_bits + wl.t_bits
-    per_token = (wl.head_dim // 2) * w // 8 + (wl.head_dim // 2) * 4 / wl.group_tokens + wl.head_dim * 2
+    v_bytes = wl.head_dim * 2 if v_bits == 16 else wl.head_dim * v_bits // 8 + 4
+    per_token = (wl.head_dim // 2) * w // 8 + (wl.head_dim // 2) * 4 / wl.group_tokens + v_bytes
     return int(round(float(lens.astype("int64").sum()) * wl.n_kv_heads * per_token))
 
 
@@ -107,6 +108,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="gqa", choices=["gqa", "mha", "long33", "ragged", "tiny"])
+    ap.add_argument("--v-bits", type=int, default=16, choices=[16, 4, 2],
+                    help="value precision: 16 = fp16 values (the headline configuration), 4 / 2 = token-wise quantized")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     args = ap.parse_args()
@@ -126,8 +129,9 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     wl = W.WORKLOADS[args.workload]
     t0 = time.time()
-    cache = build_device_cache(wl, progress=lambda s: print(f"[bench] encoded sequence {s + 1}/{wl.n_seqs}",
-                                                            file=sys.stderr, flush=True))
+    cache = build_device_cache(wl, v_bits=args.v_bits,
+                               progress=lambda s: print(f"[bench] encoded sequence {s + 1}/{wl.n_seqs}",
+                                                        file=sys.stderr, flush=True))
     torch.cuda.synchronize()
     print(f"[bench] inputs ready in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
     lens = cache.lens
@@ -138,7 +142,8 @@ def main() -> int:
 
     def partials_only():
         pq.pq_decode_partials(cache.layout, cache.q, cache.codes, cache.params, cache.values, cache.block_table,
-                              cache.seq_lens, cache.max_seq_len, cache.sm_scale, cache.workspace)
+                              cache.seq_lens, cache.max_seq_len, cache.sm_scale, cache.workspace,
+                              v_bits=cache.v_bits, v_params=cache.v_params)
 
     def merge_only():
         pq.pq_decode_merge(cache.layout, wl.n_seqs, wl.n_q_heads, cache.seq_lens, cache.max_seq_len, out,
@@ -183,7 +188,7 @@ def main() -> int:
     del probe
 
     keys_scored = int(lens.astype(np.int64).sum()) * wl.n_q_heads
-    alg_bytes = algorithmic_bytes(wl, lens)
+    alg_bytes = algorithmic_bytes(wl, lens, args.v_bits)
     achieved = alg_bytes / (ms_partials * 1e-3) / 1e9
     result = {
         "metric": "decode keys scored/sec on polar-quantized cache",
@@ -195,12 +200,14 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.n_seqs} seqs x {wl.n_q_heads} q heads over {wl.n_kv_heads} kv heads, "
                                f"head_dim {wl.head_dim}, context {wl.min_len}..{wl.max_len}, r{wl.r_bits}/t{wl.t_bits}, "
-                               f"group {wl.group_tokens}, fp16 values, RoPE base {wl.rope_base:g}",
+                               f"group {wl.group_tokens}, {'fp16' if args.v_bits == 16 else str(args.v_bits) + '-bit'} values, "
+                               f"RoPE base {wl.rope_base:g}",
                    "keys_scored_per_step": keys_scored,
                    "kv_tokens_per_step": int(lens.astype(np.int64).sum()) * wl.n_kv_heads},
         "roofline": {"bound": "hbm", "kernel": "pq_decode_partials_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": read_traffic_note(wl.name), "algorithmic_bytes": alg_bytes,
+                     "traffic": read_traffic_note(wl.name) if args.v_bits == 16 else None,
+                     "algorithmic_bytes": alg_bytes,
                      "ms_per_launch": ms_partials, "ms_merge_kernel": ms_merge,
                      "read_stream_GBps": read_stream_gbps,
                      "frac_of_read_stream": achieved / read_stream_gbps,

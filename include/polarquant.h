@@ -41,6 +41,15 @@
  *   value pool  : [page][kv_head][token g][d] fp16        (values stay fp16, Section 4.1)
  * Slots of a sequence's last page beyond its length hold zero bytes in the
  * codes pool; their values are never read.
+ *
+ * Optional quantized values (Section 2's token-wise quantizer, used in Section 6.3): b = 4 or 2
+ * bits per element, code = Clamp(round((v - z) / s), 0, 2^b - 1) with z = min and
+ * s = (max - min) / (2^b - 1) over the d values of one token of one head (round half to even;
+ * s, z stored as fp16 and used as stored); dequantized value = code * s + z.
+ *   vq pool     : [page][kv_head][token block = token / T][dim slice = dim / 8][unit 16 bytes],
+ *                 T = 16 / b tokens per unit; token i of the unit is the 8*b-bit field i of the
+ *                 unit, dim k of that token the b-bit field k of it (little-endian)
+ *   vq params   : [page][kv_head][token g]{fp16 s, fp16 z}
  */
 #ifndef POLARQUANT_H
 #define POLARQUANT_H
@@ -84,6 +93,10 @@ size_t pq_codes_bytes_per_page(const pq_layout* layout);
 size_t pq_params_bytes_per_page(const pq_layout* layout);
 size_t pq_values_bytes_per_page(const pq_layout* layout);
 
+/* Quantized values: bytes of one page of the code pool (v_bits 4 or 2) and of the parameter pool. */
+size_t pq_vq_bytes_per_page(const pq_layout* layout, int32_t v_bits);
+size_t pq_vq_params_bytes_per_page(const pq_layout* layout);
+
 /* Bytes of scratch pq_decode_attention needs for n_seqs sequences of at most
  * max_seq_len tokens (256-byte aligned device memory); 0 on invalid arguments. */
 size_t pq_decode_workspace_bytes(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
@@ -112,6 +125,18 @@ int pq_encode_keys(const pq_layout* layout, const void* keys, pq_dtype key_dtype
                    int64_t n_pool_pages, void* hip_stream);
 
 /*
+ * pq_encode_values -- token-wise value quantizer (Section 2; see the layout above).
+ *   values        device fp16, element i of KV head h of token n at values[n * token_stride +
+ *                 h * head_stride + i] (strides in elements, multiples of 8; 16-byte aligned)
+ *   v_bits        4 or 2
+ *   page_ids      device int32 [ceil(n_tokens / g)]; pages outside [0, n_pool_pages) are skipped
+ *   vq_pool, vq_params_pool   device; whole pages are written, slots past n_tokens with zeros
+ */
+int pq_encode_values(const pq_layout* layout, int32_t v_bits, const void* values, int64_t token_stride,
+                     int64_t head_stride, int64_t n_tokens, const int32_t* page_ids, void* vq_pool,
+                     void* vq_params_pool, int64_t n_pool_pages, void* hip_stream);
+
+/*
  * pq_decode_attention -- one decode step per sequence against the packed cache
  * (Section 3.3 / Appendix A for the table-lookup query-key product; softmax and
  * fp16 value aggregation are standard attention, Section 2).
@@ -126,6 +151,10 @@ int pq_encode_keys(const pq_layout* layout, const void* keys, pq_dtype key_dtype
  *                 lengths above max_seq_len are treated as max_seq_len
  *   max_seq_len   host-known upper bound of seq_lens (sizes the launch);
  *                 ceil(max_seq_len / g) <= max_pages_per_seq
+ *   v_pool, v_bits, v_params_pool
+ *                 v_bits 16: v_pool is the fp16 value pool, v_params_pool is ignored (NULL);
+ *                 v_bits 4 or 2: v_pool is the quantized value pool and v_params_pool its
+ *                 parameter pool (built for (r_bits, t_bits) = (4,4) and (3,3))
  *   n_pool_pages  pool size in pages; a block-table entry outside [0, n_pool_pages)
  *                 makes that page count as masked (no read happens)
  *   sm_scale      softmax scale (1/sqrt(d) for standard attention)
@@ -145,7 +174,8 @@ int pq_encode_keys(const pq_layout* layout, const void* keys, pq_dtype key_dtype
  */
 int pq_decode_attention(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
                         int32_t n_q_heads, const void* codes_pool, const void* params_pool,
-                        const void* v_pool, int64_t n_pool_pages, const int32_t* block_table,
+                        const void* v_pool, int32_t v_bits, const void* v_params_pool,
+                        int64_t n_pool_pages, const int32_t* block_table,
                         int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
                         float sm_scale, float* out, float* scores, int64_t scores_stride,
                         const void* residual_keys, void* workspace, size_t workspace_bytes,
@@ -161,7 +191,8 @@ int pq_decode_attention(const pq_layout* layout, const void* q, pq_dtype q_dtype
  */
 int pq_decode_partials(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
                        int32_t n_q_heads, const void* codes_pool, const void* params_pool,
-                       const void* v_pool, int64_t n_pool_pages, const int32_t* block_table,
+                       const void* v_pool, int32_t v_bits, const void* v_params_pool,
+                       int64_t n_pool_pages, const int32_t* block_table,
                        int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
                        float sm_scale, float* scores, int64_t scores_stride, const void* residual_keys,
                        void* workspace, size_t workspace_bytes, void* hip_stream);

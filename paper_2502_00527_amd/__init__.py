@@ -22,6 +22,7 @@ __all__ = [
     "pq_version", "pq_strerror", "pq_codes_bytes_per_page", "pq_params_bytes_per_page",
     "pq_values_bytes_per_page", "pq_decode_workspace_bytes", "pq_encode_keys",
     "pq_decode_attention", "pq_decode_partials", "pq_decode_merge", "pq_score_keys", "pq_append_keys",
+    "pq_vq_bytes_per_page", "pq_vq_params_bytes_per_page", "pq_encode_values",
     "pq_probe_read_stream",
 ]
 
@@ -58,11 +59,15 @@ _SIGNATURES = {
     "pq_encode_keys": (c_int, [_LP, c_void_p, c_int, c_int64, c_int64, c_int64, c_void_p, c_void_p,
                                c_void_p, c_int64, c_void_p]),
     "pq_decode_attention": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
-                                    c_int64, c_void_p, c_int32, c_void_p, c_int32, c_float, c_void_p,
+                                    c_int32, c_void_p, c_int64, c_void_p, c_int32, c_void_p, c_int32, c_float, c_void_p,
                                     c_void_p, c_int64, c_void_p, c_void_p, c_size_t, c_void_p]),
     "pq_decode_partials": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
-                                   c_int64, c_void_p, c_int32, c_void_p, c_int32, c_float, c_void_p,
+                                   c_int32, c_void_p, c_int64, c_void_p, c_int32, c_void_p, c_int32, c_float, c_void_p,
                                    c_int64, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "pq_vq_bytes_per_page": (c_size_t, [_LP, c_int32]),
+    "pq_vq_params_bytes_per_page": (c_size_t, [_LP]),
+    "pq_encode_values": (c_int, [_LP, c_int32, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p,
+                                 c_int64, c_void_p]),
     "pq_append_keys": (c_int, [_LP, c_void_p, c_int, c_int32, c_void_p, c_void_p, c_void_p, c_int32,
                                c_void_p, c_void_p, c_int64, c_void_p]),
     "pq_decode_merge": (c_int, [_LP, c_int32, c_int32, c_void_p, c_int32, c_void_p, c_void_p, c_size_t,
@@ -163,29 +168,38 @@ def pq_encode_keys(layout: Layout, keys, page_ids, codes_pool, params_pool) -> N
     _check(st, "pq_encode_keys")
 
 
-def _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens):
+def _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens, v_bits=16, v_params=None):
     import torch
     if q.dim() != 3 or q.shape[2] != layout.head_dim:
         raise PolarQuantError("q must be [n_seqs, n_q_heads, head_dim]")
-    n_pool_pages = v_pool.numel() * v_pool.element_size() // max(1, pq_values_bytes_per_page(layout))
+    n_pool_pages = codes_pool.numel() * codes_pool.element_size() // max(1, pq_codes_bytes_per_page(layout))
+    if v_bits == 16:
+        v_ptr, vp_ptr = _dev_ptr(v_pool, "v_pool", (torch.float16,)), None
+        n_v_pages = v_pool.numel() * v_pool.element_size() // max(1, pq_values_bytes_per_page(layout))
+    else:
+        v_ptr, vp_ptr = _dev_ptr(v_pool, "v_pool", (torch.uint8,)), _dev_ptr(v_params, "v_params", (torch.float16,))
+        n_v_pages = v_pool.numel() // max(1, pq_vq_bytes_per_page(layout, v_bits))
+    if n_v_pages < n_pool_pages:
+        raise PolarQuantError("value pool holds fewer pages than the codes pool")
     return dict(
         q=_dev_ptr(q, "q"), qk=_float_kind(q, "q"), n_seqs=q.shape[0], n_q=q.shape[1],
         codes=_dev_ptr(codes_pool, "codes_pool"), params=_dev_ptr(params_pool, "params_pool"),
-        v=_dev_ptr(v_pool, "v_pool", (torch.float16,)), n_pool=n_pool_pages,
+        v=v_ptr, vbits=v_bits, vpar=vp_ptr, n_pool=n_pool_pages,
         bt=_dev_ptr(block_table, "block_table", (torch.int32,)), width=block_table.shape[1],
         lens=_dev_ptr(seq_lens, "seq_lens", (torch.int32,)))
 
 
 def pq_decode_attention(layout: Layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens,
-                        max_seq_len: int, sm_scale: float, out, workspace, scores=None, residual=None) -> None:
+                        max_seq_len: int, sm_scale: float, out, workspace, scores=None, residual=None,
+                        v_bits: int = 16, v_params=None) -> None:
     """One decode step per sequence; see include/polarquant.h.  `out` fp32 [n_seqs, n_q_heads, d];
     `scores` optional fp32 [n_seqs, n_q_heads, stride >= max_seq_len]; `workspace` a uint8 device
     tensor of at least pq_decode_workspace_bytes(...) bytes."""
     import torch
-    c = _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens)
+    c = _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens, v_bits, v_params)
     st = load_library().pq_decode_attention(
         ctypes.byref(layout), c["q"], c["qk"], c["n_seqs"], c["n_q"], c["codes"], c["params"], c["v"],
-        c["n_pool"], c["bt"], c["width"], c["lens"], max_seq_len, sm_scale,
+        c["vbits"], c["vpar"], c["n_pool"], c["bt"], c["width"], c["lens"], max_seq_len, sm_scale,
         _dev_ptr(out, "out", (torch.float32,)),
         None if scores is None else _dev_ptr(scores, "scores", (torch.float32,)),
         0 if scores is None else scores.shape[-1],
@@ -195,12 +209,13 @@ def pq_decode_attention(layout: Layout, q, codes_pool, params_pool, v_pool, bloc
 
 
 def pq_decode_partials(layout: Layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens,
-                       max_seq_len: int, sm_scale: float, workspace, scores=None, residual=None) -> None:
+                       max_seq_len: int, sm_scale: float, workspace, scores=None, residual=None,
+                       v_bits: int = 16, v_params=None) -> None:
     import torch
-    c = _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens)
+    c = _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens, v_bits, v_params)
     st = load_library().pq_decode_partials(
         ctypes.byref(layout), c["q"], c["qk"], c["n_seqs"], c["n_q"], c["codes"], c["params"], c["v"],
-        c["n_pool"], c["bt"], c["width"], c["lens"], max_seq_len, sm_scale,
+        c["vbits"], c["vpar"], c["n_pool"], c["bt"], c["width"], c["lens"], max_seq_len, sm_scale,
         None if scores is None else _dev_ptr(scores, "scores", (torch.float32,)),
         0 if scores is None else scores.shape[-1],
         None if residual is None else _dev_ptr(residual, "residual", (torch.float16,)),
@@ -216,6 +231,30 @@ def pq_decode_merge(layout: Layout, n_seqs: int, n_q_heads: int, seq_lens, max_s
         _dev_ptr(out, "out", (torch.float32,)), _dev_ptr(workspace, "workspace"),
         workspace.numel() * workspace.element_size(), _stream())
     _check(st, "pq_decode_merge")
+
+
+def pq_vq_bytes_per_page(layout: Layout, v_bits: int) -> int:
+    return load_library().pq_vq_bytes_per_page(ctypes.byref(layout), v_bits)
+
+
+def pq_vq_params_bytes_per_page(layout: Layout) -> int:
+    return load_library().pq_vq_params_bytes_per_page(ctypes.byref(layout))
+
+
+def pq_encode_values(layout: Layout, v_bits: int, values, page_ids, vq_pool, vq_params) -> None:
+    """values fp16 [n_tokens, n_kv_heads, d] (last dim contiguous, device); vq_pool uint8, vq_params fp16
+    device tensors holding whole pages."""
+    import torch
+    if values.dim() != 3 or values.shape[1] != layout.n_kv_heads or values.shape[2] != layout.head_dim:
+        raise PolarQuantError("values must be [n_tokens, n_kv_heads, head_dim]")
+    if values.dtype != torch.float16 or values.stride(2) != 1 or not values.is_cuda:
+        raise PolarQuantError("values must be a device fp16 tensor with a contiguous last dimension")
+    n_pool_pages = vq_pool.numel() // max(1, pq_vq_bytes_per_page(layout, v_bits))
+    st = load_library().pq_encode_values(
+        ctypes.byref(layout), v_bits, values.data_ptr(), values.stride(0), values.stride(1), values.shape[0],
+        _dev_ptr(page_ids, "page_ids", (torch.int32,)), _dev_ptr(vq_pool, "vq_pool", (torch.uint8,)),
+        _dev_ptr(vq_params, "vq_params", (torch.float16,)), n_pool_pages, _stream())
+    _check(st, "pq_encode_values")
 
 
 def pq_append_keys(layout: Layout, new_keys, residual, seq_lens, block_table, codes_pool, params_pool) -> None:

@@ -68,16 +68,27 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert lib.pq_encode_keys(ctypes.byref(lay), null, 0, 1024, 128, 0, null, null, null, 4, null) == 0
     bad = pq.Layout(128, 7, 1, 128, 8)
     assert lib.pq_encode_keys(ctypes.byref(bad), null, 0, 1024, 128, 10, null, null, null, 4, null) == -2
-    st = lib.pq_decode_attention(ctypes.byref(lay), null, 0, 1, 32, null, null, null, 4, null, 1, null, 128,
+    st = lib.pq_decode_attention(ctypes.byref(lay), null, 0, 1, 32, null, null, null, 16, null, 4, null, 1, null, 128,
                                  0.1, null, null, 0, null, null, 0, null)
     assert st == -1
     fake = ctypes.c_void_p(4096)
-    st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 4, fake, 1, fake, 128,
+    st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 16, null, 4, fake, 1, fake, 128,
                                 0.1, null, 0, null, null, 0, null)
     assert st == -3 and "workspace" in pq.pq_strerror(st)
     # more pages needed than the block table is wide
-    st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 4, fake, 1, fake, 129,
+    st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 16, null, 4, fake, 1, fake, 129,
                                 0.1, null, 0, null, fake, 1 << 20, null)
+    assert st == -1
+    # quantized values need their parameter pool; 3-bit values are not built
+    st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 4, null, 4, fake, 1, fake, 128,
+                                0.1, null, 0, null, fake, 1 << 20, null)
+    assert st == -1
+    st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 3, fake, 4, fake, 1, fake, 128,
+                                0.1, null, 0, null, fake, 1 << 20, null)
+    assert st == -2
+    assert pq.pq_vq_bytes_per_page(lay, 4) == 8 * 128 * 64 and pq.pq_vq_bytes_per_page(lay, 2) == 8 * 128 * 32
+    assert pq.pq_vq_bytes_per_page(lay, 3) == 0 and pq.pq_vq_params_bytes_per_page(lay) == 8 * 128 * 4
+    st = lib.pq_encode_values(ctypes.byref(lay), 4, null, 1024, 128, 10, null, null, null, 4, null)
     assert st == -1
     st = lib.pq_append_keys(ctypes.byref(lay), null, 0, 4, null, null, null, 8, null, null, 16, null)
     assert st == -1

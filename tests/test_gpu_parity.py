@@ -181,6 +181,49 @@ def test_score_keys_entry_point(name):
         assert torch.isnan(got[s, :, L:]).all(), "scores past the sequence end must stay untouched"
 
 
+@pytest.mark.parametrize("case", [("gqa_ragged_tail", 4), ("gqa_ragged_tail", 2), ("tiny_full_config", 4),
+                                  ("long33", 2), ("group_of_two", 4), ("edge_lengths", 4), ("ragged_pages", 2)])
+def test_quantized_values(case):
+    """Token-wise 4/2-bit values: pq_encode_values bit-exact against the oracle's quantizer and
+    packer; decode attention over them within the output bar of the oracle's attention over the
+    dequantized values."""
+    from oracle import cache_format, values as ovalues
+    from paper_2502_00527_amd.cache import build_device_cache
+
+    name, v_bits = case
+    wl, lens = SMALL[name]
+    cache = build_device_cache(wl, lens=lens, v_bits=v_bits)
+    _say(f"[parity] quantized values {name} v{v_bits}: decode launch")
+    out = cache.decode().cpu().numpy()
+    torch.cuda.synchronize()
+    q_h = W.queries(wl)
+    g = wl.group_tokens
+    worst = 0.0
+    for s in range(wl.n_seqs):
+        L = int(cache.lens[s])
+        if L <= 0:
+            assert not out[s].any()
+            continue
+        n_pages = (L + g - 1) // g
+        ids = torch.from_numpy(cache.table[s, :n_pages].astype(np.int64)).to("cuda:0")
+        vals = W.values_for_seq(wl, s, L)
+        vc, vs, vz = ovalues.quantize_values(vals, v_bits)
+        want_pool = cache_format.pack_value_page_stream(vc, v_bits, g)
+        np.testing.assert_array_equal(cache.values[ids].cpu().numpy(), want_pool, err_msg="value codes differ")
+        par = np.zeros((n_pages * g, wl.n_kv_heads, 2), np.float16)
+        par[:L, :, 0], par[:L, :, 1] = vs, vz
+        want_par = par.reshape(n_pages, g, wl.n_kv_heads, 2).transpose(0, 2, 1, 3)
+        np.testing.assert_array_equal(cache.v_params[ids].cpu().numpy().view(np.uint16), want_par.view(np.uint16),
+                                      err_msg="value scale / zero-point bits differ")
+        ref = OracleSeq(wl, s, L)
+        _, _, k_hat = ref.attend(q_h[s], cache.sm_scale)
+        from oracle import attention as oattention
+        _, ref_out = oattention.attend(q_h[s].astype(np.float64), k_hat, ovalues.dequant_values(vc, vs, vz), cache.sm_scale)
+        worst = max(worst, float(np.abs(out[s] - ref_out).max()))
+    _say(f"[parity] quantized values {name} v{v_bits}: max_out_err={worst:.3e}")
+    assert worst <= OUT_ABS
+
+
 def test_block_table_entry_outside_pool_is_masked():
     """A page id outside the pool makes that page count as masked: nothing is read for it and the
     result is attention over the remaining tokens."""
