@@ -142,8 +142,9 @@ int pq_encode_values(const pq_layout* layout, int32_t v_bits, const void* values
  * fp16 value aggregation are standard attention, Section 2).
  *
  *   q             device [n_seqs][n_q_heads][d], post-RoPE, q_dtype PQ_F16 or PQ_F32.
- *                 Query head h reads KV head h / (n_q_heads / n_kv_heads); the ratio
- *                 must be 1, 2 or 4
+ *                 Query head h reads KV head h / (n_q_heads / n_kv_heads); the ratio may be
+ *                 1 .. 16.  Kernels serve 4, 2 or 1 query heads per pass over the cache, so a
+ *                 ratio of 1, 2 or 4 reads the cache once, 8 twice, 6 = 4 + 2 twice, ...
  *   block_table   device int32 [n_seqs][max_pages_per_seq]: page of tokens
  *                 [i*g, (i+1)*g) of each sequence; entries past a sequence's last page
  *                 are ignored

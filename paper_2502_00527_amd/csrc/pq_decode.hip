@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
     for (int i = 0; i < 8; ++i) cu[i] = load_unit<W>(rc_cur, voff_codes, i * 16 * UB);
   }
   {
-    const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * G) * kHeadDim;
+    const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim;
     float* lf = reinterpret_cast<float*>(lut);
     for (int idx = tid; idx < kPairs * NA; idx += kThreads) {
       const int j = idx >> TB, s = idx & (NA - 1);
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
   }
   __syncthreads();
 
-  float* const out_row = a.scores + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * G + my_head) * a.scores_stride;
+  float* const out_row = a.scores + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0 + my_head) * a.scores_stride;
   for (int i = 0; i < n_w; ++i) {
     const int pi = page0 + wave + kWaves * i;
     if (i + 1 < n_w) {
@@ -248,7 +248,7 @@ int check_decode_shape(const pq_layout* l, int32_t n_seqs, int32_t n_q_heads, in
   if (l->n_kv_heads <= 0 || n_q_heads % l->n_kv_heads != 0) return PQ_ERR_INVALID_ARG;
   if (!layout_supported(l)) return PQ_ERR_UNSUPPORTED;
   const int G = n_q_heads / l->n_kv_heads;
-  if (G != 1 && G != 2 && G != 4) return PQ_ERR_UNSUPPORTED;
+  if (G > 16) return PQ_ERR_UNSUPPORTED;   // groups are processed 4, 2 or 1 query heads per pass
   if (n_seqs > 65535 || n_q_heads > 65535) return PQ_ERR_UNSUPPORTED;   // grid.y, merge grid.x
   return PQ_OK;
 }
@@ -317,22 +317,31 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
 
   const dim3 grid(layout->n_kv_heads, n_seqs, plan.n_chunks);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const int G = n_q_heads / layout->n_kv_heads;
+  const int group_total = n_q_heads / layout->n_kv_heads;
   hipError_t e = hipSuccess;
   const int rt = layout->r_bits * 10 + layout->t_bits;
-  if (v_bits != 16) {
-    e = launch_partials_vq(rt, G, v_bits, a, q_dtype, grid, stream);
-    if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;   // quantized values: (r,t) = (4,4), (3,3) only
-  } else {
-    switch (rt) {
-      case 44: e = launch_partials_g<4, 4>(G, a, q_dtype, grid, stream); break;
-      case 33: e = launch_partials_g<3, 3>(G, a, q_dtype, grid, stream); break;
-      case 53: e = launch_partials_g<5, 3>(G, a, q_dtype, grid, stream); break;
-      case 35: e = launch_partials_g<3, 5>(G, a, q_dtype, grid, stream); break;
-      case 42: e = launch_partials_g<4, 2>(G, a, q_dtype, grid, stream); break;
-      case 24: e = launch_partials_g<2, 4>(G, a, q_dtype, grid, stream); break;
-      default: return PQ_ERR_UNSUPPORTED;
+  // A kernel instance serves 4, 2 or 1 query heads of a KV head; larger or odd groups take
+  // several passes over the cache (6 = 4 + 2, 8 = 4 + 4, ...).
+  a.group_total = group_total;
+  for (int head0 = 0; head0 < group_total && e == hipSuccess;) {
+    const int left = group_total - head0;
+    const int G = left >= 4 ? 4 : (left >= 2 ? 2 : 1);
+    a.head0 = head0;
+    if (v_bits != 16) {
+      e = launch_partials_vq(rt, G, v_bits, a, q_dtype, grid, stream);
+      if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;   // quantized values: (r,t) = (4,4), (3,3) only
+    } else {
+      switch (rt) {
+        case 44: e = launch_partials_g<4, 4>(G, a, q_dtype, grid, stream); break;
+        case 33: e = launch_partials_g<3, 3>(G, a, q_dtype, grid, stream); break;
+        case 53: e = launch_partials_g<5, 3>(G, a, q_dtype, grid, stream); break;
+        case 35: e = launch_partials_g<3, 5>(G, a, q_dtype, grid, stream); break;
+        case 42: e = launch_partials_g<4, 2>(G, a, q_dtype, grid, stream); break;
+        case 24: e = launch_partials_g<2, 4>(G, a, q_dtype, grid, stream); break;
+        default: return PQ_ERR_UNSUPPORTED;
+      }
     }
+    head0 += G;
   }
   if (e != hipSuccess) return record_hip_error(e);
   return PQ_OK;
@@ -405,16 +414,23 @@ extern "C" int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_
   fill_angle_tables(a, layout->t_bits);
   const dim3 grid(layout->n_kv_heads, n_seqs, plan.n_chunks);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const int G = n_q_heads / layout->n_kv_heads;
+  const int group_total = n_q_heads / layout->n_kv_heads;
   hipError_t e = hipSuccess;
-  switch (layout->r_bits * 10 + layout->t_bits) {
-    case 44: e = launch_scores<4, 4>(G, a, q_dtype, grid, stream); break;
-    case 33: e = launch_scores<3, 3>(G, a, q_dtype, grid, stream); break;
-    case 53: e = launch_scores<5, 3>(G, a, q_dtype, grid, stream); break;
-    case 35: e = launch_scores<3, 5>(G, a, q_dtype, grid, stream); break;
-    case 42: e = launch_scores<4, 2>(G, a, q_dtype, grid, stream); break;
-    case 24: e = launch_scores<2, 4>(G, a, q_dtype, grid, stream); break;
-    default: return PQ_ERR_UNSUPPORTED;
+  a.group_total = group_total;
+  for (int head0 = 0; head0 < group_total && e == hipSuccess;) {
+    const int left = group_total - head0;
+    const int G = left >= 4 ? 4 : (left >= 2 ? 2 : 1);
+    a.head0 = head0;
+    switch (layout->r_bits * 10 + layout->t_bits) {
+      case 44: e = launch_scores<4, 4>(G, a, q_dtype, grid, stream); break;
+      case 33: e = launch_scores<3, 3>(G, a, q_dtype, grid, stream); break;
+      case 53: e = launch_scores<5, 3>(G, a, q_dtype, grid, stream); break;
+      case 35: e = launch_scores<3, 5>(G, a, q_dtype, grid, stream); break;
+      case 42: e = launch_scores<4, 2>(G, a, q_dtype, grid, stream); break;
+      case 24: e = launch_scores<2, 4>(G, a, q_dtype, grid, stream); break;
+      default: return PQ_ERR_UNSUPPORTED;
+    }
+    head0 += G;
   }
   if (e != hipSuccess) return record_hip_error(e);
   return PQ_OK;

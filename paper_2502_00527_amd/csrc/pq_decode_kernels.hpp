@@ -57,6 +57,8 @@ struct DecodeArgs {
   int64_t n_pool_pages;
   int32_t n_kv_heads;
   int32_t n_q_heads;
+  int32_t group_total;      // query heads per KV head (any value); one launch covers G of them ...
+  int32_t head0;            // ... starting at this head of the group
   int32_t max_pages_per_seq;
   int32_t max_seq_len;
   int32_t pages_per_chunk;
@@ -511,7 +513,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   // ---- table of the G query heads that share this KV head (Section 3.3) ----
   // (built while the first page's loads, issued above, are in flight)
   {
-    const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * G) * kHeadDim;
+    const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim;
     float* lf = reinterpret_cast<float*>(lut);
     for (int idx = tid; idx < kPairs * NA; idx += kThreads) {
       const int j = idx >> TB, s = idx & (NA - 1);
@@ -607,7 +609,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
       const int tok = t * 16 + col;
       if constexpr (SCORES) {
         if (owner && tok < nv_cur)
-          a.scores[(static_cast<int64_t>(seq) * a.n_q_heads + kvh * G + my_head) * a.scores_stride +
+          a.scores[(static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0 + my_head) * a.scores_stride +
                    static_cast<int64_t>(pi) * kGroup + tok] = sc[t];
       }
       sc[t] = (tok < nv_cur) ? sc[t] * a.scale_log2 : kNegInf;
@@ -719,7 +721,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
         l = fmaf(wgt, red_ml[w][h][1], l);
       }
     }
-    const int64_t slot = (static_cast<int64_t>(seq) * a.n_q_heads + kvh * G + h) * a.n_chunks + chunk;
+    const int64_t slot = (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0 + h) * a.n_chunks + chunk;
     a.ws_acc[slot * kHeadDim + dim] = o;
     if (dim == 0) {
       a.ws_ml[slot * 2] = M;

@@ -57,7 +57,8 @@ def test_workspace_size_follows_the_chunk_plan(lib):
     assert pq.pq_decode_workspace_bytes(lay, 1, 32, 1) > 0
     assert pq.pq_decode_workspace_bytes(lay, 0, 32, 128) == 0
     assert pq.pq_decode_workspace_bytes(lay, 1, 12, 128) == 0      # 12 query heads over 8 kv heads
-    assert pq.pq_decode_workspace_bytes(lay, 1, 64, 128) == 0      # group of 8 not built
+    assert pq.pq_decode_workspace_bytes(lay, 1, 64, 128) > 0       # group of 8: two passes of 4
+    assert pq.pq_decode_workspace_bytes(lay, 1, 8 * 17, 128) == 0  # group of 17 not served
 
 
 def test_argument_errors_are_reported_before_any_launch(lib):

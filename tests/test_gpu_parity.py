@@ -41,6 +41,9 @@ SMALL = {
     "bits_r4t2": (WL["gqa"].scaled(n_seqs=1, n_q_heads=2, n_kv_heads=1, max_len=777, min_len=777, r_bits=4, t_bits=2), None),
     "bits_r2t4": (WL["gqa"].scaled(n_seqs=1, n_q_heads=1, n_kv_heads=1, max_len=777, min_len=777, r_bits=2, t_bits=4), None),
     "tiny33_fp32": (WL["tiny"].scaled(max_len=1500, min_len=1500, r_bits=3, t_bits=3), None),
+    "group_of_six": (WL["gqa"].scaled(n_seqs=2, n_q_heads=12, n_kv_heads=2, max_len=650, min_len=650), None),   # 4 + 2
+    "group_of_seven": (WL["gqa"].scaled(n_seqs=1, n_q_heads=7, n_kv_heads=1, max_len=400, min_len=400, r_bits=3, t_bits=3), None),
+    "group_of_eight": (WL["gqa"].scaled(n_seqs=1, n_q_heads=16, n_kv_heads=2, max_len=520, min_len=520), None),  # 4 + 4
 }
 
 
@@ -151,7 +154,8 @@ def test_results_are_deterministic():
     assert torch.equal(oa, ob)
 
 
-@pytest.mark.parametrize("name", ["gqa_ragged_tail", "tiny33_fp32", "group_of_two", "ragged_pages", "bits_r5t3"])
+@pytest.mark.parametrize("name", ["gqa_ragged_tail", "tiny33_fp32", "group_of_two", "ragged_pages", "bits_r5t3",
+                                  "group_of_six"])
 def test_score_keys_entry_point(name):
     """pq_score_keys (the query-key product alone) against the oracle's dequantize-then-dot scores,
     and against the scores pq_decode_attention reports for the same cache."""
@@ -182,7 +186,8 @@ def test_score_keys_entry_point(name):
 
 
 @pytest.mark.parametrize("case", [("gqa_ragged_tail", 4), ("gqa_ragged_tail", 2), ("tiny_full_config", 4),
-                                  ("long33", 2), ("group_of_two", 4), ("edge_lengths", 4), ("ragged_pages", 2)])
+                                  ("long33", 2), ("group_of_two", 4), ("edge_lengths", 4), ("ragged_pages", 2),
+                                  ("group_of_seven", 4)])
 def test_quantized_values(case):
     """Token-wise 4/2-bit values: pq_encode_values bit-exact against the oracle's quantizer and
     packer; decode attention over them within the output bar of the oracle's attention over the
