@@ -22,7 +22,9 @@ def dequant_sequence(codes_pool, params_pool, page_ids, length, r_bits, t_bits, 
                      residual_seq=None):
     """Keys float64 [length, H, d] of one sequence as the decode step sees them.
 
-    codes_pool uint8 [n_pool_pages, H, P/16, g, 2w]; params_pool fp16 [n_pool_pages, H, P, 2];
+    codes_pool uint8 [n_pool_pages, H, P/16, g, 2w]; params_pool fp16 [n_pool_pages, H, P, 2], or
+    [n_pool_pages, H, 2, P, 2] when the angles were quantized group-wise (radius, then angle
+    parameters: the angle levels are then the group's own);
     page_ids: the sequence's pages in order.  Without a residual buffer every token is
     reconstructed from the packed pages.  With one (fp16 [H, g, d]; Appendix B.1: recent keys
     stay un-quantized until a full group exists) only the complete groups are, and the keys of
@@ -32,15 +34,15 @@ def dequant_sequence(codes_pool, params_pool, page_ids, length, r_bits, t_bits, 
     if residual_seq is None:
         n_pages = (length + g - 1) // g
         ids = np.asarray(page_ids[:n_pages], np.int64)
-        a, c, scale, zero = cache_format.unpack_pages(codes_pool[ids], params_pool[ids], length, r_bits, t_bits)
-        return polar.dequant_keys(a, c, scale, zero, t_bits, g)
+        a, c, *par = cache_format.unpack_pages(codes_pool[ids], params_pool[ids], length, r_bits, t_bits)
+        return polar.dequant_keys(a, c, par[0], par[1], t_bits, g, *par[2:])
     n_full = length // g
     rest = length - n_full * g
     parts = []
     if n_full:
         ids = np.asarray(page_ids[:n_full], np.int64)
-        a, c, scale, zero = cache_format.unpack_pages(codes_pool[ids], params_pool[ids], n_full * g, r_bits, t_bits)
-        parts.append(polar.dequant_keys(a, c, scale, zero, t_bits, g))
+        a, c, *par = cache_format.unpack_pages(codes_pool[ids], params_pool[ids], n_full * g, r_bits, t_bits)
+        parts.append(polar.dequant_keys(a, c, par[0], par[1], t_bits, g, *par[2:]))
     if rest:
         parts.append(np.asarray(residual_seq)[:, :rest, :].transpose(1, 0, 2).astype(np.float64))
     return np.concatenate(parts, axis=0)

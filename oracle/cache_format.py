@@ -12,6 +12,8 @@ its public header and the two write-ups share no code.
                 string is bit (i % 8) of byte (i // 8).  A unit is 2*w bytes.
   codes page  = [kv_head][pair_block = pair // 16][token_in_page][unit]
   params page = [kv_head][pair]{fp16 scale, fp16 zero}
+                with the grouped angle quantizer: [kv_head][2][pair]{fp16 scale, fp16 zero},
+                the radius parameters first, then the angle parameters
   value page  = [kv_head][token_in_page][d] fp16
 
 A page holds `g` tokens (one quantization group).  Slots of a partial last
@@ -57,11 +59,13 @@ def unpack_units(units: np.ndarray, r_bits: int, t_bits: int):
     return sym >> r_bits, sym & ((1 << r_bits) - 1)
 
 
-def pack_sequence(a, c, scale, zero, r_bits: int, t_bits: int, group_tokens: int):
+def pack_sequence(a, c, scale, zero, r_bits: int, t_bits: int, group_tokens: int, t_scale=None, t_zero=None):
     """Pages of one sequence.
 
-    a, c: [L, H, P] codes; scale, zero: fp16 [n_pages, H, P].
-    Returns (codes uint8 [n_pages, H, P/16, g, 2w], params fp16 [n_pages, H, P, 2]).
+    a, c: [L, H, P] codes; scale, zero (and t_scale, t_zero of the grouped angle quantizer):
+    fp16 [n_pages, H, P].
+    Returns (codes uint8 [n_pages, H, P/16, g, 2w], params fp16 [n_pages, H, P, 2], or
+    [n_pages, H, 2, P, 2] with angle parameters).
     """
     L, H, P = a.shape
     assert P % PAIRS_PER_UNIT == 0
@@ -76,6 +80,9 @@ def pack_sequence(a, c, scale, zero, r_bits: int, t_bits: int, group_tokens: int
         n0, n1 = p * g, min((p + 1) * g, L)
         codes[p, :, :, : n1 - n0, :] = units[n0:n1].transpose(1, 2, 0, 3)
     params = np.stack([scale.astype(np.float16), zero.astype(np.float16)], axis=-1)
+    if t_scale is not None:
+        t_params = np.stack([t_scale.astype(np.float16), t_zero.astype(np.float16)], axis=-1)
+        params = np.stack([params, t_params], axis=2)
     return codes, params
 
 
@@ -83,12 +90,15 @@ def unpack_pages(codes: np.ndarray, params: np.ndarray, length: int, r_bits: int
     """Inverse of pack_sequence for the pages of one sequence, in order.
 
     codes uint8 [n_pages, H, P/16, g, 2w]; params fp16 [n_pages, H, P, 2].
-    Returns (a, c) int64 [length, H, P] and (scale, zero) fp16 [n_pages, H, P].
+    Returns (a, c) int64 [length, H, P] and (scale, zero) fp16 [n_pages, H, P]; for params of
+    shape [n_pages, H, 2, P, 2] (grouped angle quantizer) also (t_scale, t_zero).
     """
     n_pages, H, nb, g, _ = codes.shape
     a, c = unpack_units(codes, r_bits, t_bits)                            # [n_pages, H, nb, g, 16]
     a = a.transpose(0, 3, 1, 2, 4).reshape(n_pages * g, H, nb * PAIRS_PER_UNIT)[:length]
     c = c.transpose(0, 3, 1, 2, 4).reshape(n_pages * g, H, nb * PAIRS_PER_UNIT)[:length]
+    if params.ndim == 5:
+        return a, c, params[:, :, 0, :, 0], params[:, :, 0, :, 1], params[:, :, 1, :, 0], params[:, :, 1, :, 1]
     return a, c, params[..., 0], params[..., 1]
 
 
@@ -96,8 +106,8 @@ def codes_bytes_per_page(n_kv_heads: int, head_dim: int, r_bits: int, t_bits: in
     return n_kv_heads * group_tokens * (head_dim // 2) * (r_bits + t_bits) // 8
 
 
-def params_bytes_per_page(n_kv_heads: int, head_dim: int) -> int:
-    return n_kv_heads * (head_dim // 2) * 2 * 2
+def params_bytes_per_page(n_kv_heads: int, head_dim: int, grouped_angles: bool = False) -> int:
+    return n_kv_heads * (head_dim // 2) * 2 * 2 * (2 if grouped_angles else 1)
 
 
 def pack_value_page_stream(codes: np.ndarray, bits: int, group_tokens: int) -> np.ndarray:

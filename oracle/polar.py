@@ -25,6 +25,17 @@ Follows Section 3.2 of the paper step by step, with these readings fixed:
   division; Q = 0 when s == 0.
 * Dequantizer: rho~ = (Q + 1/2) s + z and theta~ = -pi + (Q_theta + 1/2) D,
   key~ = (rho~ cos theta~, rho~ sin theta~) at dims (j, j + d/2).
+
+Grouped angle quantizer (Section 3.2 as printed: the angle is quantized like the
+radius, asymmetric and group-wise; the appendix listing rebuilds the angle
+levels from "tscale" and "tmn" per group):
+* theta = atan2(y, x) in float64, in [-pi, pi].  The printed "+ pi" would only
+  add pi to every zero-point; it is dropped, so that cos / sin of the
+  reconstructed angle give the key back and not its negative.
+* per pair and group: z = min theta, s = (max - min) / 2^t over the valid
+  tokens, both stored as fp16 (rounded once, from float64, to nearest even),
+  Q = Clamp(floor((theta - z) / s), 0, 2^t - 1) against the stored values in
+  float64, Q = 0 when s == 0;  theta~ = (Q + 1/2) s + z.
 """
 from __future__ import annotations
 
@@ -120,7 +131,47 @@ def radius_codes(rho: np.ndarray, scale: np.ndarray, zero: np.ndarray, group_tok
     return np.clip(q, 0, (1 << r_bits) - 1).astype(np.int64)
 
 
-def encode_keys(keys: np.ndarray, r_bits: int, t_bits: int, group_tokens: int, param_dtype=np.float16):
+def angle_group_params(theta: np.ndarray, group_tokens: int, t_bits: int, param_dtype=np.float16):
+    """Per (group, head, pair) scale and zero-point of the grouped angle quantizer.
+
+    theta: float64 [L, H, P] = atan2(y, x).  Same grouping as radius_group_params.
+    Returns (scale, zero) of dtype param_dtype, shape [ceil(L/g), H, P].
+    """
+    L = theta.shape[0]
+    n_groups = (L + group_tokens - 1) // group_tokens
+    scale = np.empty((n_groups,) + theta.shape[1:], param_dtype)
+    zero = np.empty_like(scale)
+    for k in range(n_groups):
+        blk = theta[k * group_tokens: min((k + 1) * group_tokens, L)]
+        mn = blk.min(axis=0)
+        mx = blk.max(axis=0)
+        scale[k] = ((mx - mn) / F64(1 << t_bits)).astype(param_dtype)
+        zero[k] = mn.astype(param_dtype)
+    return scale, zero
+
+
+def angle_group_codes(theta: np.ndarray, scale: np.ndarray, zero: np.ndarray, group_tokens: int, t_bits: int):
+    """Q(theta) = Clamp(floor((theta - z) / s), 0, 2^t - 1) against the stored parameters.
+
+    Returns (code int64, edge_dist float64): edge_dist is the distance in radians from theta
+    to the nearest boundary between two bins of its group's grid (z + k s, 0 < k < 2^t).
+    """
+    n_bins = 1 << t_bits
+    grp = np.arange(theta.shape[0]) // group_tokens
+    s = scale.astype(F64)[grp]
+    z = zero.astype(F64)[grp]
+    with np.errstate(divide="ignore", invalid="ignore"):
+        u = (theta - z) / s
+    u = np.where(s == 0, 0.0, u)
+    code = np.clip(np.floor(u), 0, n_bins - 1).astype(np.int64)
+    nearest = np.clip(np.rint(u), 1, n_bins - 1)           # interior boundaries only
+    edge_dist = np.abs(u - nearest) * s
+    edge_dist = np.where(s == 0, np.inf, edge_dist)
+    return code, edge_dist
+
+
+def encode_keys(keys: np.ndarray, r_bits: int, t_bits: int, group_tokens: int, param_dtype=np.float16,
+                grouped_angles: bool = False):
     """Encode post-RoPE keys [L, H, d] of one sequence.
 
     Returns a dict with
@@ -129,13 +180,20 @@ def encode_keys(keys: np.ndarray, r_bits: int, t_bits: int, group_tokens: int, p
       scale, zero  param_dtype [ceil(L/g), H, P]
       rho   float32 [L, H, P] (for audits)
       edge_dist float64 [L, H, P] distance of theta to the nearest bin edge, radians
+    and, with grouped_angles (the paper's own angle quantizer instead of the uniform grid),
+      t_scale, t_zero  param_dtype [ceil(L/g), H, P]
     """
     x, y = split_pairs(keys)
     rho = radius_f32(x, y)
-    a, edge = angle_bin(x, y, t_bits)
     scale, zero = radius_group_params(rho, group_tokens, r_bits, param_dtype)
     c = radius_codes(rho, scale, zero, group_tokens, r_bits)
-    return dict(a=a, c=c, scale=scale, zero=zero, rho=rho, edge_dist=edge)
+    if not grouped_angles:
+        a, edge = angle_bin(x, y, t_bits)
+        return dict(a=a, c=c, scale=scale, zero=zero, rho=rho, edge_dist=edge)
+    theta = np.arctan2(y.astype(F64), x.astype(F64))
+    t_scale, t_zero = angle_group_params(theta, group_tokens, t_bits, param_dtype)
+    a, edge = angle_group_codes(theta, t_scale, t_zero, group_tokens, t_bits)
+    return dict(a=a, c=c, scale=scale, zero=zero, rho=rho, edge_dist=edge, t_scale=t_scale, t_zero=t_zero)
 
 
 def dequant_radius(c: np.ndarray, scale: np.ndarray, zero: np.ndarray, group_tokens: int) -> np.ndarray:
@@ -149,8 +207,16 @@ def dequant_angle(a: np.ndarray, t_bits: int) -> np.ndarray:
     return -np.pi + (a.astype(F64) + 0.5) * (2.0 * np.pi / (1 << t_bits))
 
 
-def dequant_keys(a, c, scale, zero, t_bits: int, group_tokens: int) -> np.ndarray:
-    """Reconstructed keys float64 [L, H, d]: (rho~ cos theta~, rho~ sin theta~) at dims (j, j+d/2)."""
+def dequant_angle_grouped(a: np.ndarray, t_scale: np.ndarray, t_zero: np.ndarray, group_tokens: int) -> np.ndarray:
+    """theta~ = (Q + 1/2) * s + z in float64 with the group's angle parameters."""
+    grp = np.arange(a.shape[0]) // group_tokens
+    return (a.astype(F64) + 0.5) * t_scale.astype(F64)[grp] + t_zero.astype(F64)[grp]
+
+
+def dequant_keys(a, c, scale, zero, t_bits: int, group_tokens: int, t_scale=None, t_zero=None) -> np.ndarray:
+    """Reconstructed keys float64 [L, H, d]: (rho~ cos theta~, rho~ sin theta~) at dims (j, j+d/2).
+
+    With t_scale / t_zero the angle levels are the group's own (grouped angle quantizer)."""
     rho = dequant_radius(c, scale, zero, group_tokens)
-    th = dequant_angle(a, t_bits)
+    th = dequant_angle(a, t_bits) if t_scale is None else dequant_angle_grouped(a, t_scale, t_zero, group_tokens)
     return np.concatenate([rho * np.cos(th), rho * np.sin(th)], axis=-1)
