@@ -50,6 +50,18 @@
  *                 T = 16 / b tokens per unit; token i of the unit is the 8*b-bit field i of the
  *                 unit, dim k of that token the b-bit field k of it (little-endian)
  *   vq params   : [page][kv_head][token g]{fp16 s, fp16 z}
+ *
+ * Optional grouped angle quantizer (pq_layout.angle_quantizer = PQ_ANGLE_GROUPED): the angle
+ * quantizer exactly as Section 3.2 prints it, asymmetric and group-wise like the radius, instead of
+ * the uniform grid.  theta = atan2(y, x) in float64 (the printed "+ pi" would only shift every
+ * zero-point and is dropped); per pair and group z = min theta, s = (max - min) / 2^t over the
+ * valid tokens, rounded once to fp16 and used as rounded;
+ *   angle code a = Clamp(floor((theta - z) / s), 0, 2^t - 1) in float64, a = 0 if s == 0
+ *   reconstruction theta~ = (a + 1/2) s + z
+ * so the lookup table of Section 3.3 is rebuilt from (s, z) for every group (the appendix listing
+ * does the same from "tscale" and "tmn").  The parameter block of a page doubles:
+ *   params pool : [page][kv_head][2][pair P]{fp16 s, fp16 z}   radius parameters, then angle parameters
+ * Available for (r, t) = (4, 4) and (3, 3).
  */
 #ifndef POLARQUANT_H
 #define POLARQUANT_H
@@ -71,16 +83,23 @@ typedef enum {
 
 typedef enum { PQ_F16 = 0, PQ_F32 = 1 } pq_dtype;
 
+typedef enum {
+  PQ_ANGLE_UNIFORM = 0,      /* uniform grid of 2^t bins over [-pi, pi), no angle parameters */
+  PQ_ANGLE_GROUPED = 1       /* per-group min / scale (Section 3.2 as printed) */
+} pq_angle_quantizer;
+
 /* Shape of the packed cache.  Plain data, passed by const pointer.
  * Supported: head_dim 128; (r_bits, t_bits) with r + t in {6, 8}, 2 <= r, t <= 5
  * -- (4,4) and (3,3) are the paper's main settings, the others its bit
- * allocation ablation (Section 6.1); group_tokens 128; any n_kv_heads >= 1. */
+ * allocation ablation (Section 6.1); group_tokens 128; any n_kv_heads >= 1;
+ * angle_quantizer PQ_ANGLE_UNIFORM, or PQ_ANGLE_GROUPED with (4,4) or (3,3). */
 typedef struct {
-  int32_t head_dim;      /* d */
-  int32_t r_bits;        /* radius bits r */
-  int32_t t_bits;        /* angle bits t */
-  int32_t group_tokens;  /* g: tokens per quantization group = tokens per page */
+  int32_t head_dim;         /* d */
+  int32_t r_bits;           /* radius bits r */
+  int32_t t_bits;           /* angle bits t */
+  int32_t group_tokens;     /* g: tokens per quantization group = tokens per page */
   int32_t n_kv_heads;
+  int32_t angle_quantizer;  /* a pq_angle_quantizer */
 } pq_layout;
 
 int pq_version(void);

@@ -36,10 +36,11 @@ class PolarQuantError(RuntimeError):
 
 
 class Layout(ctypes.Structure):
-    """pq_layout: head_dim, r_bits, t_bits, group_tokens, n_kv_heads."""
+    """pq_layout: head_dim, r_bits, t_bits, group_tokens, n_kv_heads, angle_quantizer
+    (0 = uniform grid, 1 = the paper's grouped min/scale quantizer)."""
 
     _fields_ = [("head_dim", c_int32), ("r_bits", c_int32), ("t_bits", c_int32),
-                ("group_tokens", c_int32), ("n_kv_heads", c_int32)]
+                ("group_tokens", c_int32), ("n_kv_heads", c_int32), ("angle_quantizer", c_int32)]
 
 
 def lib_path() -> str:
@@ -152,6 +153,15 @@ def pq_decode_workspace_bytes(layout: Layout, n_seqs: int, n_q_heads: int, max_s
     return load_library().pq_decode_workspace_bytes(ctypes.byref(layout), n_seqs, n_q_heads, max_seq_len)
 
 
+def _key_pool_pages(layout: Layout, codes_pool, params_pool) -> int:
+    """Pages the codes pool holds; the parameter pool must hold as many (its page size doubles
+    with the grouped angle quantizer)."""
+    n = codes_pool.numel() * codes_pool.element_size() // max(1, pq_codes_bytes_per_page(layout))
+    if params_pool.numel() * params_pool.element_size() < n * pq_params_bytes_per_page(layout):
+        raise PolarQuantError("params pool holds fewer pages than the codes pool")
+    return n
+
+
 def pq_encode_keys(layout: Layout, keys, page_ids, codes_pool, params_pool) -> None:
     """keys [n_tokens, n_kv_heads, d] (last dim contiguous, fp16/fp32, device); page_ids int32
     [ceil(n_tokens/g)] device; pools uint8 device tensors holding whole pages."""
@@ -160,7 +170,7 @@ def pq_encode_keys(layout: Layout, keys, page_ids, codes_pool, params_pool) -> N
         raise PolarQuantError("keys must be [n_tokens, n_kv_heads, head_dim]")
     if keys.stride(2) != 1 or not keys.is_cuda:
         raise PolarQuantError("keys must be a device tensor with a contiguous last dimension")
-    n_pool_pages = codes_pool.numel() * codes_pool.element_size() // max(1, pq_codes_bytes_per_page(layout))
+    n_pool_pages = _key_pool_pages(layout, codes_pool, params_pool)
     st = load_library().pq_encode_keys(
         ctypes.byref(layout), keys.data_ptr(), _float_kind(keys, "keys"), keys.stride(0), keys.stride(1),
         keys.shape[0], _dev_ptr(page_ids, "page_ids", (torch.int32,)), _dev_ptr(codes_pool, "codes_pool"),
@@ -172,7 +182,7 @@ def _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_
     import torch
     if q.dim() != 3 or q.shape[2] != layout.head_dim:
         raise PolarQuantError("q must be [n_seqs, n_q_heads, head_dim]")
-    n_pool_pages = codes_pool.numel() * codes_pool.element_size() // max(1, pq_codes_bytes_per_page(layout))
+    n_pool_pages = _key_pool_pages(layout, codes_pool, params_pool)
     if v_bits == 16:
         v_ptr, vp_ptr = _dev_ptr(v_pool, "v_pool", (torch.float16,)), None
         n_v_pages = v_pool.numel() * v_pool.element_size() // max(1, pq_values_bytes_per_page(layout))
@@ -263,7 +273,7 @@ def pq_append_keys(layout: Layout, new_keys, residual, seq_lens, block_table, co
     import torch
     if new_keys.dim() != 3 or new_keys.shape[1] != layout.n_kv_heads or new_keys.shape[2] != layout.head_dim:
         raise PolarQuantError("new_keys must be [n_seqs, n_kv_heads, head_dim]")
-    n_pool_pages = codes_pool.numel() * codes_pool.element_size() // max(1, pq_codes_bytes_per_page(layout))
+    n_pool_pages = _key_pool_pages(layout, codes_pool, params_pool)
     st = load_library().pq_append_keys(
         ctypes.byref(layout), _dev_ptr(new_keys, "new_keys"), _float_kind(new_keys, "new_keys"), new_keys.shape[0],
         _dev_ptr(residual, "residual", (torch.float16,)), _dev_ptr(seq_lens, "seq_lens", (torch.int32,)),
@@ -278,7 +288,7 @@ def pq_score_keys(layout: Layout, q, codes_pool, params_pool, block_table, seq_l
     import torch
     if q.dim() != 3 or q.shape[2] != layout.head_dim:
         raise PolarQuantError("q must be [n_seqs, n_q_heads, head_dim]")
-    n_pool_pages = codes_pool.numel() * codes_pool.element_size() // max(1, pq_codes_bytes_per_page(layout))
+    n_pool_pages = _key_pool_pages(layout, codes_pool, params_pool)
     st = load_library().pq_score_keys(
         ctypes.byref(layout), _dev_ptr(q, "q"), _float_kind(q, "q"), q.shape[0], q.shape[1],
         _dev_ptr(codes_pool, "codes_pool"), _dev_ptr(params_pool, "params_pool"), n_pool_pages,

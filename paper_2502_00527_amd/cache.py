@@ -25,7 +25,7 @@ class DeviceCache:
     table: np.ndarray                # host int32 [S, width]
     n_pool_pages: int
     codes: torch.Tensor              # uint8 [pages, H, P/16, g, 2w]
-    params: torch.Tensor             # fp16  [pages, H, P, 2]
+    params: torch.Tensor             # fp16  [pages, H, P, 2], or [pages, H, 2, P, 2] with grouped angles
     values: torch.Tensor             # fp16  [pages, H, g, d], or uint8 [pages, H, g/T, d/8, 16] when quantized
     v_bits: int                      # 16, 4 or 2
     v_params: Optional[torch.Tensor] # fp16 [pages, H, g, 2] (scale, zero) when quantized
@@ -51,7 +51,7 @@ class DeviceCache:
 
 
 def make_layout(wl: W.Workload) -> Layout:
-    return Layout(wl.head_dim, wl.r_bits, wl.t_bits, wl.group_tokens, wl.n_kv_heads)
+    return Layout(wl.head_dim, wl.r_bits, wl.t_bits, wl.group_tokens, wl.n_kv_heads, 1 if wl.grouped_angles else 0)
 
 
 def build_device_cache(wl: W.Workload, device="cuda:0", lens: Optional[np.ndarray] = None,
@@ -67,10 +67,11 @@ def build_device_cache(wl: W.Workload, device="cuda:0", lens: Optional[np.ndarra
     g, H, d = wl.group_tokens, wl.n_kv_heads, wl.head_dim
     ub = 2 * (wl.r_bits + wl.t_bits)
     assert pq_codes_bytes_per_page(layout) == H * (d // 32) * g * ub
-    assert pq_params_bytes_per_page(layout) == H * (d // 2) * 4
+    par_shape = (total, H, 2, d // 2, 2) if wl.grouped_angles else (total, H, d // 2, 2)
+    assert pq_params_bytes_per_page(layout) == int(np.prod(par_shape[1:])) * 2
     # poison the pools so that a slot the encoder should have written shows up
     codes = torch.full((total, H, d // 32, g, ub), 0xA5, dtype=torch.uint8, device=device)
-    params = torch.full((total, H, d // 2, 2), float("nan"), dtype=torch.float16, device=device)
+    params = torch.full(par_shape, float("nan"), dtype=torch.float16, device=device)
     v_params = None
     if v_bits == 16:
         values = torch.full((total, H, g, d), float("nan"), dtype=torch.float16, device=device)

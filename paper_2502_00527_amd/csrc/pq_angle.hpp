@@ -69,4 +69,20 @@ PQ_HD inline uint32_t angle_bin(float x, float y, const double* tan_edge) {
   return origin * (NB / 2) + (1u ^ origin) * code;
 }
 
+// v rounded to the nearest fp16 value, ties to even, returned as a double (|v| < 65504).  One
+// rounding, straight from float64: the quantum is 2^(e - 10) for |v| in [2^e, 2^(e+1)), and 2^-24
+// below the smallest normal fp16.  Used for the 16-bit parameters of the grouped angle quantizer,
+// whose statistics are float64.
+PQ_HD inline double round_to_half(double v) {
+  uint64_t b;
+  __builtin_memcpy(&b, &v, 8);
+  int e = static_cast<int>((b >> 52) & 0x7ffu) - 1023;
+  if (e < -14) e = -14;
+  const uint64_t qb = static_cast<uint64_t>(e - 10 + 1023) << 52, ib = static_cast<uint64_t>(10 - e + 1023) << 52;
+  double q, iq;
+  __builtin_memcpy(&q, &qb, 8);
+  __builtin_memcpy(&iq, &ib, 8);
+  return rint(v * iq) * q;         // both scalings are exact (powers of two)
+}
+
 }  // namespace pq

@@ -20,6 +20,8 @@ bool layout_supported(const pq_layout* l) {
   if (l->head_dim != kHeadDim || l->group_tokens != kGroup || l->n_kv_heads < 1) return false;
   const int r = l->r_bits, t = l->t_bits, w = r + t;
   if (r < 2 || r > 5 || t < 2 || t > 5) return false;
+  if (l->angle_quantizer == PQ_ANGLE_GROUPED) return r == t && (r == 4 || r == 3);
+  if (l->angle_quantizer != PQ_ANGLE_UNIFORM) return false;
   return w == 6 || w == 8;
 }
 
@@ -63,7 +65,7 @@ __global__ __launch_bounds__(256) void pq_read_stream_kernel(const uint4* __rest
 
 using namespace pq;
 
-extern "C" int pq_version(void) { return 100; }
+extern "C" int pq_version(void) { return 101; }
 
 extern "C" const char* pq_strerror(int status) {
   switch (status) {
@@ -85,7 +87,7 @@ extern "C" size_t pq_codes_bytes_per_page(const pq_layout* l) {
 
 extern "C" size_t pq_params_bytes_per_page(const pq_layout* l) {
   if (!layout_supported(l)) return 0;
-  return static_cast<size_t>(l->n_kv_heads) * kPairs * 4;
+  return static_cast<size_t>(l->n_kv_heads) * kPairs * 4 * (l->angle_quantizer == PQ_ANGLE_GROUPED ? 2 : 1);
 }
 
 extern "C" size_t pq_values_bytes_per_page(const pq_layout* l) {

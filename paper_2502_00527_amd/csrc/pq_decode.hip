@@ -1,5 +1,5 @@
-// Host entry points of the decode path (pq_decode_*, pq_score_keys), the chunk merge kernel and
-// the score-only kernel.  The attention kernel template lives in pq_decode_kernels.hpp.
+// Host entry points of the decode path (pq_decode_*, pq_score_keys) and the chunk merge kernel.
+// The attention and score-only kernel templates live in pq_decode_kernels.hpp.
 #include "pq_decode_kernels.hpp"
 
 namespace pq {
@@ -59,123 +59,6 @@ __global__ __launch_bounds__(kHeadDim) void pq_decode_merge_kernel(
     }
     const float inv = lt > 0.f ? 1.f / lt : 0.f;
     reinterpret_cast<float4*>(out + oh * kHeadDim)[quad] = make_float4(r.x * inv, r.y * inv, r.z * inv, r.w * inv);
-  }
-}
-
-// ---- query-key scores only (the kernel the paper times in Section 5.2) ------------------
-// Same table, same page walk and same pair steps as the attention kernel, without softmax and
-// values: every wavefront scores its pages and stores the raw q . k~ of valid tokens.
-template <int G, int RB, int TB, typename QT>
-__global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArgs a) {
-  constexpr int W = RB + TB;
-  constexpr int UB = 2 * W;
-  constexpr int NA = 1 << TB;
-  constexpr int ROW = NA * 16;
-  __shared__ __attribute__((aligned(16))) uint8_t lut[kPairs * ROW];
-
-  const int kvh = blockIdx.x, seq = blockIdx.y, chunk = blockIdx.z;
-  const int L = min(a.seq_lens[seq], a.max_seq_len);
-  if (L <= 0) return;
-  const int n_pages = (L + kGroup - 1) / kGroup;
-  const int page0 = chunk * a.pages_per_chunk;
-  if (page0 >= n_pages) return;
-  const int npg = min(a.pages_per_chunk, n_pages - page0);
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int row = lane >> 4, col = lane & 15;
-  const int my_head = (G == 4) ? row : (G == 2 ? (row >> 1) : 0);
-  const bool owner = (G == 4) || (G == 2 && (row & 1) == 0) || (G == 1 && row == 0);
-  const uint32_t lut_row0 = lds_addr(lut) + row * (kPairsPerUnit * ROW);
-  const uint32_t voff_codes = (row * kGroup + col) * UB;
-  const uint32_t voff_params = row * (kPairsPerUnit * 4);
-  constexpr uint32_t kCodesBytes = kBlocks * kGroup * UB;
-
-  const int n_w = npg > wave ? (npg - wave + kWaves - 1) / kWaves : 0;
-  int pid_lane = -1;
-  if (lane < n_w) {
-    const int64_t pid = a.block_table[static_cast<int64_t>(seq) * a.max_pages_per_seq + page0 + wave + kWaves * lane];
-    if (pid >= 0 && pid < a.n_pool_pages) pid_lane = static_cast<int>(pid);
-  }
-  auto page_setup = [&](int k, __amdgpu_buffer_rsrc_t& rc, __amdgpu_buffer_rsrc_t& rp, int& nv) {
-    const int pid = __builtin_amdgcn_readlane(pid_lane, k);
-    const bool ok = pid >= 0;
-    const int64_t ph = ok ? static_cast<int64_t>(pid) * a.n_kv_heads + kvh : 0;
-    nv = ok ? min(kGroup, L - (page0 + wave + kWaves * k) * kGroup) : 0;
-    rc = make_rsrc(a.codes + ph * kCodesBytes, ok ? kCodesBytes : 0u);
-    rp = make_rsrc(a.params + ph * kPairs, ok ? kPairs * 4u : 0u);
-  };
-  const __amdgpu_buffer_rsrc_t rs_empty = make_rsrc(a.codes, 0u);
-  __amdgpu_buffer_rsrc_t rc_cur = rs_empty, rp_cur = rs_empty, rc_nxt = rs_empty, rp_nxt = rs_empty;
-  int nv_cur = 0, nv_nxt = 0;
-  uint4 praw[4];
-  Unit<W / 2> cu[8];
-  if (n_w > 0) {
-    page_setup(0, rc_cur, rp_cur, nv_cur);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) praw[i] = buf_load16<kAuxCached>(rp_cur, voff_params, i * 16);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) cu[i] = load_unit<W>(rc_cur, voff_codes, i * 16 * UB);
-  }
-  {
-    const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim;
-    float* lf = reinterpret_cast<float*>(lut);
-    for (int idx = tid; idx < kPairs * NA; idx += kThreads) {
-      const int j = idx >> TB, s = idx & (NA - 1);
-      const float cs = a.cos_tab[s], sn = a.sin_tab[s];
-#pragma unroll
-      for (int h = 0; h < G; ++h) {
-        const float qx = static_cast<float>(qb[h * kHeadDim + j]);
-        const float qy = static_cast<float>(qb[h * kHeadDim + j + kPairs]);
-        lf[idx * 4 + h] = fmaf(qx, cs, qy * sn);
-      }
-    }
-  }
-  __syncthreads();
-
-  float* const out_row = a.scores + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0 + my_head) * a.scores_stride;
-  for (int i = 0; i < n_w; ++i) {
-    const int pi = page0 + wave + kWaves * i;
-    if (i + 1 < n_w) {
-      page_setup(i + 1, rc_nxt, rp_nxt, nv_nxt);
-    } else {
-      rc_nxt = rp_nxt = rs_empty;
-      nv_nxt = 0;
-    }
-    float sf[16], zz[16];
-#pragma unroll
-    for (int v4 = 0; v4 < 4; ++v4) {
-      const uint32_t w4[4] = {praw[v4].x, praw[v4].y, praw[v4].z, praw[v4].w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const __half2 sz = *reinterpret_cast<const __half2*>(&w4[e]);
-        const float s = __low2float(sz), z = __high2float(sz);
-        sf[v4 * 4 + e] = s;
-        zz[v4 * 4 + e] = fmaf(0.5f, s, z);
-      }
-    }
-#pragma unroll
-    for (int v4 = 0; v4 < 4; ++v4) praw[v4] = buf_load16<kAuxCached>(rp_nxt, voff_params, v4 * 16);
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      float part[G];
-#pragma unroll
-      for (int h = 0; h < G; ++h) part[h] = 0.f;
-      score_steps<G, RB, TB, 0>(cu[s], lut_row0, sf, zz, part);
-      cu[s] = load_unit<W>(rc_nxt, voff_codes, s * 16 * UB);       // next page's pass s
-      float sc;
-      if constexpr (G == 4) {
-        sc = tsum16(tsum32(part[0], part[2]), tsum32(part[1], part[3]));
-      } else if constexpr (G == 2) {
-        const float b = tsum32(part[0], part[1]);
-        sc = tsum16(b, b);
-      } else {
-        sc = sum_rows(part[0]);
-      }
-      const int tok = s * 16 + col;
-      if (owner && tok < nv_cur) out_row[static_cast<int64_t>(pi) * kGroup + tok] = sc;
-    }
-    rc_cur = rc_nxt; rp_cur = rp_nxt; nv_cur = nv_nxt;
   }
 }
 
@@ -327,7 +210,11 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
     const int left = group_total - head0;
     const int G = left >= 4 ? 4 : (left >= 2 ? 2 : 1);
     a.head0 = head0;
-    if (v_bits != 16) {
+    if (layout->angle_quantizer == PQ_ANGLE_GROUPED) {
+      if (v_bits != 16) return PQ_ERR_UNSUPPORTED;                // grouped angles: fp16 values only
+      e = launch_partials_ga(rt, G, a, q_dtype, grid, stream);
+      if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;
+    } else if (v_bits != 16) {
       e = launch_partials_vq(rt, G, v_bits, a, q_dtype, grid, stream);
       if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;   // quantized values: (r,t) = (4,4), (3,3) only
     } else {
@@ -421,6 +308,12 @@ extern "C" int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_
     const int left = group_total - head0;
     const int G = left >= 4 ? 4 : (left >= 2 ? 2 : 1);
     a.head0 = head0;
+    if (layout->angle_quantizer == PQ_ANGLE_GROUPED) {
+      e = launch_scores_ga(layout->r_bits * 10 + layout->t_bits, G, a, q_dtype, grid, stream);
+      if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;
+      head0 += G;
+      continue;
+    }
     switch (layout->r_bits * 10 + layout->t_bits) {
       case 44: e = launch_scores<4, 4>(G, a, q_dtype, grid, stream); break;
       case 33: e = launch_scores<3, 3>(G, a, q_dtype, grid, stream); break;

@@ -25,6 +25,11 @@
 // A last step folds the four wavefronts' (m, l, acc) into one partial per
 // (sequence, query head, chunk); pq_decode_merge_kernel combines the chunks.
 // No MFMA: the hot loop is a gather-accumulate.
+//
+// Grouped angle quantizer (Section 3.2 as printed; template flag GA): the angle levels of a
+// group are theta~_a = (a + 1/2) s_t + z_t with the group's own (s_t, z_t), so every wavefront
+// keeps a table of its own in LDS and rebuilds it from the page's angle parameters before it
+// scores the page (the appendix listing builds the same table from "tscale" and "tmn").
 #pragma once
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
@@ -73,6 +78,10 @@ struct DecodeArgs {
 // kernel for the combination.
 hipError_t launch_partials_vq(int rt, int G, int v_bits, const DecodeArgs& a, pq_dtype qdt, dim3 grid,
                               hipStream_t st);
+// The attention and score-only kernels for the grouped angle quantizer (fp16 values; (r,t) =
+// (4,4) or (3,3)); defined in pq_decode_ga.hip.  hipErrorInvalidValue if there is no kernel.
+hipError_t launch_partials_ga(int rt, int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st);
+hipError_t launch_scores_ga(int rt, int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st);
 
 namespace {
 
@@ -383,17 +392,48 @@ __device__ __forceinline__ void consume_quantized(const uint4& u, int tok0, uint
   }
 }
 
-template <int G, int RB, int TB, typename QT, bool SCORES, int VB>
+// Grouped angle quantizer: this wavefront's table T[j][a][h] = q_x[h][j] cos(theta~) + q_y[h][j]
+// sin(theta~), theta~ = (a + 1/2) s_t[j] + z_t[j] (Section 3.2 reconstruction, Section 3.3 table),
+// for the page whose angle parameters {fp16 s_t, fp16 z_t} of pair `lane` are in `tpar`.
+// Entry e = 64 * it + lane = (pair e >> t, state e & (2^t - 1)): consecutive lanes write
+// consecutive 16-byte entries.  q_addr is the LDS byte address of q[dim][4 heads].
+template <int TB>
+__device__ __forceinline__ void build_group_table(uint32_t lut_w, uint32_t tpar, uint32_t q_addr, int lane) {
+  constexpr int NA = 1 << TB;
+  const float level = static_cast<float>(lane & (NA - 1)) + 0.5f;
+#pragma unroll
+  for (int it = 0; it < NA; ++it) {
+    const int j = it * (64 >> TB) + (lane >> TB);
+    const uint32_t p = static_cast<uint32_t>(__shfl(static_cast<int>(tpar), j));
+    const __half2 sz = *reinterpret_cast<const __half2*>(&p);
+    const float rev = fmaf(level, __low2float(sz), __high2float(sz)) * 0.15915494309189535f;   // turns
+    const float cs = __builtin_amdgcn_cosf(rev), sn = __builtin_amdgcn_sinf(rev);
+    const f32x4 qx = *(const PQ_LDS f32x4*)static_cast<uintptr_t>(q_addr + j * 16);
+    const f32x4 qy = *(const PQ_LDS f32x4*)static_cast<uintptr_t>(q_addr + (j + kPairs) * 16);
+    f32x4 t;
+    t.x = fmaf(qx.x, cs, qy.x * sn);
+    t.y = fmaf(qx.y, cs, qy.y * sn);
+    t.z = fmaf(qx.z, cs, qy.z * sn);
+    t.w = fmaf(qx.w, cs, qy.w * sn);
+    *(PQ_LDS f32x4*)static_cast<uintptr_t>(lut_w + (it * 64 + lane) * 16) = t;
+  }
+}
+
+template <int G, int RB, int TB, typename QT, bool SCORES, int VB, bool GA = false>
 __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   constexpr int W = RB + TB;
   constexpr int UB = 2 * W;              // bytes per unit
   constexpr int NA = 1 << TB;            // angle states
   constexpr int ROW = NA * 16;           // table bytes per pair
 
-  __shared__ __attribute__((aligned(16))) uint8_t lut[kPairs * ROW];
+  // one table per work-group, or (GA) one per wavefront; with GA the wavefront's table space is
+  // reused for its accumulators in the final fold, which keeps two work-groups per compute unit
+  constexpr int kLutBytes = kPairs * ROW;
+  __shared__ __attribute__((aligned(16))) uint8_t lut[(GA ? kWaves : 1) * kLutBytes];
   __shared__ __attribute__((aligned(16))) float prob[kWaves][kGroup * G];
   __shared__ __attribute__((aligned(16))) float alpha_s[kWaves][4];
-  __shared__ __attribute__((aligned(16))) float red_acc[kWaves][G][kHeadDim];
+  __shared__ __attribute__((aligned(16))) float red_own[GA ? 4 : kWaves * G * kHeadDim];
+  static_assert(!GA || kLutBytes >= G * kHeadDim * 4, "table space too small for the accumulators");
   __shared__ float red_ml[kWaves][G][3];                              // m, l, sum of p * zero-point
   __shared__ __attribute__((aligned(16))) float q_lds[kHeadDim][4];   // q[dim][head] for residual keys
   __shared__ float res_sc[kGroup * G];                                // raw scores of the residual group
@@ -426,7 +466,11 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
 
-  const uint32_t lut_row0 = lds_addr(lut) + row * (kPairsPerUnit * ROW);
+  const uint32_t lut_w = lds_addr(lut) + (GA ? wave * kLutBytes : 0);
+  const uint32_t lut_row0 = lut_w + row * (kPairsPerUnit * ROW);
+  auto red_acc = [&](int w) -> float* {   // [G][kHeadDim] accumulators of wavefront w in the final fold
+    return GA ? reinterpret_cast<float*>(lut + w * kLutBytes) : red_own + w * (G * kHeadDim);
+  };
   const uint32_t pw_addr = lds_addr(prob[wave]);
   const uint32_t voff_codes = (row * kGroup + col) * UB;          // unit of (block row, token col) of pass 0
   const uint32_t voff_params = row * (kPairsPerUnit * 4);
@@ -446,6 +490,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   // Buffer descriptors of the wavefront's k-th page; a masked page gets empty descriptors
   // (every read returns zero) and zero valid tokens.
   constexpr bool kQuantV = VB != 16;
+  constexpr int kParamSets = GA ? 2 : 1;   // radius parameters (+ angle parameters) per pair
   constexpr int kVLoads = kQuantV ? kGroup * kHeadDim * VB / 8 / 1024 : 32;   // 1 KB wave-loads per page
   constexpr int kTokPerLoad = kGroup / kVLoads;                              // 16 (4 bit), 32 (2 bit)
   auto page_setup = [&](int k, __amdgpu_buffer_rsrc_t& rc, __amdgpu_buffer_rsrc_t& rp,
@@ -456,7 +501,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
     nv = ok ? min(kGroup, L - (page0 + wave + kWaves * k) * kGroup) : 0;
     const bool packed = ok && (page0 + wave + kWaves * k) != res_page;   // the residual group has no codes yet
     rc = make_rsrc(a.codes + ph * kCodesBytes, packed ? kCodesBytes : 0u);
-    rp = make_rsrc(a.params + ph * kPairs, packed ? kPairs * 4u : 0u);
+    rp = make_rsrc(a.params + ph * (kPairs * kParamSets), packed ? kPairs * 4u * kParamSets : 0u);
     if constexpr (kQuantV) {
       // whole units are read; codes of slots past the sequence end are finite by construction
       // and meet a zero probability.  Their parameters could be anything: bounded by nv.
@@ -484,6 +529,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   __amdgpu_buffer_rsrc_t rc_nxt = rs_empty, rp_nxt = rs_empty, rv_nxt = rs_empty, rvp_nxt = rs_empty;
   int nv_cur = 0, nv_nxt = 0;
   uint4 praw[4];
+  uint32_t tpar = 0;                                               // GA: angle parameters of pair `lane`
   Unit<W / 2> cu[8];
   constexpr int kRingSets = PQ_RING_SETS;                          // register quads of 4 value rows in flight
   uint4 ring[kRingSets][4];                                        // fp16 values
@@ -495,6 +541,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
     page_setup(0, rc_cur, rp_cur, rv_cur, rvp_cur, nv_cur);
 #pragma unroll
     for (int i = 0; i < 4; ++i) praw[i] = buf_load16<kAuxCached>(rp_cur, voff_params, i * 16);
+    if constexpr (GA) tpar = buf_load4<kAuxCached>(rp_cur, lane * 4, kPairs * 4);
 #pragma unroll
     for (int i = 0; i < 8; ++i) cu[i] = load_unit<W>(rc_cur, voff_codes, i * 16 * UB);
     if constexpr (kQuantV) {
@@ -514,20 +561,22 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   // (built while the first page's loads, issued above, are in flight)
   {
     const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim;
-    float* lf = reinterpret_cast<float*>(lut);
-    for (int idx = tid; idx < kPairs * NA; idx += kThreads) {
-      const int j = idx >> TB, s = idx & (NA - 1);
-      const float cs = a.cos_tab[s], sn = a.sin_tab[s];
+    if constexpr (!GA) {
+      float* lf = reinterpret_cast<float*>(lut);
+      for (int idx = tid; idx < kPairs * NA; idx += kThreads) {
+        const int j = idx >> TB, s = idx & (NA - 1);
+        const float cs = a.cos_tab[s], sn = a.sin_tab[s];
 #pragma unroll
-      for (int h = 0; h < G; ++h) {
-        const float qx = static_cast<float>(qb[h * kHeadDim + j]);
-        const float qy = static_cast<float>(qb[h * kHeadDim + j + kPairs]);
-        lf[idx * 4 + h] = fmaf(qx, cs, qy * sn);
+        for (int h = 0; h < G; ++h) {
+          const float qx = static_cast<float>(qb[h * kHeadDim + j]);
+          const float qy = static_cast<float>(qb[h * kHeadDim + j + kPairs]);
+          lf[idx * 4 + h] = fmaf(qx, cs, qy * sn);
+        }
       }
     }
     if (tid < kHeadDim) {
 #pragma unroll
-      for (int h = 0; h < G; ++h) q_lds[tid][h] = static_cast<float>(qb[h * kHeadDim + tid]);
+      for (int h = 0; h < 4; ++h) q_lds[tid][h] = h < G ? static_cast<float>(qb[h * kHeadDim + tid]) : 0.f;
     }
   }
   __syncthreads();
@@ -568,6 +617,12 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
     } else {
       rc_nxt = rp_nxt = rv_nxt = rvp_nxt = rs_empty;
       nv_nxt = 0;
+    }
+
+    if constexpr (GA) {
+      // this page's table (the previous page's was released by the barrier that ended its value phase)
+      build_group_table<TB>(lut_w, tpar, lds_addr(q_lds), lane);
+      wave_lds_sync();
     }
 
     // radius parameters of this lane's 16 pairs: rho~ = c * s + (z + s/2)
@@ -642,6 +697,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
     // ---- next page's parameters and codes, into the registers the score phase released ----
 #pragma unroll
     for (int v4 = 0; v4 < 4; ++v4) praw[v4] = buf_load16<kAuxCached>(rp_nxt, voff_params, v4 * 16);
+    if constexpr (GA) tpar = buf_load4<kAuxCached>(rp_nxt, lane * 4, kPairs * 4);
 #pragma unroll
     for (int s = 0; s < 8; ++s) cu[s] = load_unit<W>(rc_nxt, voff_codes, s * 16 * UB);
     if constexpr (kQuantV) {
@@ -700,7 +756,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) t[e] = sum_rows(acc[h][e]);
       if (row == 0) {
-        float4* dst = reinterpret_cast<float4*>(&red_acc[wave][h][col * 8]);
+        float4* dst = reinterpret_cast<float4*>(red_acc(wave) + h * kHeadDim + col * 8);
         dst[0] = make_float4(t[0], t[1], t[2], t[3]);
         dst[1] = make_float4(t[4], t[5], t[6], t[7]);
       }
@@ -717,7 +773,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) {
         const float wgt = __builtin_amdgcn_exp2f(red_ml[w][h][0] - M);
-        o = fmaf(wgt, red_acc[w][h][dim] + red_ml[w][h][2], o);
+        o = fmaf(wgt, red_acc(w)[h * kHeadDim + dim] + red_ml[w][h][2], o);
         l = fmaf(wgt, red_ml[w][h][1], l);
       }
     }
@@ -727,6 +783,142 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
       a.ws_ml[slot * 2] = M;
       a.ws_ml[slot * 2 + 1] = l;
     }
+  }
+}
+
+// ---- query-key scores only (the kernel the paper times in Section 5.2) ------------------
+// Same table, same page walk and same pair steps as the attention kernel, without softmax and
+// values: every wavefront scores its pages and stores the raw q . k~ of valid tokens.
+template <int G, int RB, int TB, typename QT, bool GA = false>
+__global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArgs a) {
+  constexpr int W = RB + TB;
+  constexpr int UB = 2 * W;
+  constexpr int NA = 1 << TB;
+  constexpr int ROW = NA * 16;
+  constexpr int kLutBytes = kPairs * ROW;
+  constexpr int kParamSets = GA ? 2 : 1;
+  __shared__ __attribute__((aligned(16))) uint8_t lut[(GA ? kWaves : 1) * kLutBytes];   // GA: one table per wavefront
+  __shared__ __attribute__((aligned(16))) float q_lds[GA ? kHeadDim : 1][4];
+
+  const int kvh = blockIdx.x, seq = blockIdx.y, chunk = blockIdx.z;
+  const int L = min(a.seq_lens[seq], a.max_seq_len);
+  if (L <= 0) return;
+  const int n_pages = (L + kGroup - 1) / kGroup;
+  const int page0 = chunk * a.pages_per_chunk;
+  if (page0 >= n_pages) return;
+  const int npg = min(a.pages_per_chunk, n_pages - page0);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int row = lane >> 4, col = lane & 15;
+  const int my_head = (G == 4) ? row : (G == 2 ? (row >> 1) : 0);
+  const bool owner = (G == 4) || (G == 2 && (row & 1) == 0) || (G == 1 && row == 0);
+  const uint32_t lut_w = lds_addr(lut) + (GA ? wave * kLutBytes : 0);
+  const uint32_t lut_row0 = lut_w + row * (kPairsPerUnit * ROW);
+  const uint32_t voff_codes = (row * kGroup + col) * UB;
+  const uint32_t voff_params = row * (kPairsPerUnit * 4);
+  constexpr uint32_t kCodesBytes = kBlocks * kGroup * UB;
+
+  const int n_w = npg > wave ? (npg - wave + kWaves - 1) / kWaves : 0;
+  int pid_lane = -1;
+  if (lane < n_w) {
+    const int64_t pid = a.block_table[static_cast<int64_t>(seq) * a.max_pages_per_seq + page0 + wave + kWaves * lane];
+    if (pid >= 0 && pid < a.n_pool_pages) pid_lane = static_cast<int>(pid);
+  }
+  auto page_setup = [&](int k, __amdgpu_buffer_rsrc_t& rc, __amdgpu_buffer_rsrc_t& rp, int& nv) {
+    const int pid = __builtin_amdgcn_readlane(pid_lane, k);
+    const bool ok = pid >= 0;
+    const int64_t ph = ok ? static_cast<int64_t>(pid) * a.n_kv_heads + kvh : 0;
+    nv = ok ? min(kGroup, L - (page0 + wave + kWaves * k) * kGroup) : 0;
+    rc = make_rsrc(a.codes + ph * kCodesBytes, ok ? kCodesBytes : 0u);
+    rp = make_rsrc(a.params + ph * (kPairs * kParamSets), ok ? kPairs * 4u * kParamSets : 0u);
+  };
+  const __amdgpu_buffer_rsrc_t rs_empty = make_rsrc(a.codes, 0u);
+  __amdgpu_buffer_rsrc_t rc_cur = rs_empty, rp_cur = rs_empty, rc_nxt = rs_empty, rp_nxt = rs_empty;
+  int nv_cur = 0, nv_nxt = 0;
+  uint4 praw[4];
+  uint32_t tpar = 0;
+  Unit<W / 2> cu[8];
+  if (n_w > 0) {
+    page_setup(0, rc_cur, rp_cur, nv_cur);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) praw[i] = buf_load16<kAuxCached>(rp_cur, voff_params, i * 16);
+    if constexpr (GA) tpar = buf_load4<kAuxCached>(rp_cur, lane * 4, kPairs * 4);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) cu[i] = load_unit<W>(rc_cur, voff_codes, i * 16 * UB);
+  }
+  {
+    const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim;
+    if constexpr (GA) {
+      if (tid < kHeadDim) {
+#pragma unroll
+        for (int h = 0; h < 4; ++h) q_lds[tid][h] = h < G ? static_cast<float>(qb[h * kHeadDim + tid]) : 0.f;
+      }
+    } else {
+      float* lf = reinterpret_cast<float*>(lut);
+      for (int idx = tid; idx < kPairs * NA; idx += kThreads) {
+        const int j = idx >> TB, s = idx & (NA - 1);
+        const float cs = a.cos_tab[s], sn = a.sin_tab[s];
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          const float qx = static_cast<float>(qb[h * kHeadDim + j]);
+          const float qy = static_cast<float>(qb[h * kHeadDim + j + kPairs]);
+          lf[idx * 4 + h] = fmaf(qx, cs, qy * sn);
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  float* const out_row = a.scores + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0 + my_head) * a.scores_stride;
+  for (int i = 0; i < n_w; ++i) {
+    const int pi = page0 + wave + kWaves * i;
+    if (i + 1 < n_w) {
+      page_setup(i + 1, rc_nxt, rp_nxt, nv_nxt);
+    } else {
+      rc_nxt = rp_nxt = rs_empty;
+      nv_nxt = 0;
+    }
+    if constexpr (GA) {
+      wave_lds_sync();                                             // the previous page's table is no longer read
+      build_group_table<TB>(lut_w, tpar, lds_addr(q_lds), lane);
+      wave_lds_sync();
+    }
+    float sf[16], zz[16];
+#pragma unroll
+    for (int v4 = 0; v4 < 4; ++v4) {
+      const uint32_t w4[4] = {praw[v4].x, praw[v4].y, praw[v4].z, praw[v4].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const __half2 sz = *reinterpret_cast<const __half2*>(&w4[e]);
+        const float s = __low2float(sz), z = __high2float(sz);
+        sf[v4 * 4 + e] = s;
+        zz[v4 * 4 + e] = fmaf(0.5f, s, z);
+      }
+    }
+#pragma unroll
+    for (int v4 = 0; v4 < 4; ++v4) praw[v4] = buf_load16<kAuxCached>(rp_nxt, voff_params, v4 * 16);
+    if constexpr (GA) tpar = buf_load4<kAuxCached>(rp_nxt, lane * 4, kPairs * 4);
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      float part[G];
+#pragma unroll
+      for (int h = 0; h < G; ++h) part[h] = 0.f;
+      score_steps<G, RB, TB, 0>(cu[s], lut_row0, sf, zz, part);
+      cu[s] = load_unit<W>(rc_nxt, voff_codes, s * 16 * UB);       // next page's pass s
+      float sc;
+      if constexpr (G == 4) {
+        sc = tsum16(tsum32(part[0], part[2]), tsum32(part[1], part[3]));
+      } else if constexpr (G == 2) {
+        const float b = tsum32(part[0], part[1]);
+        sc = tsum16(b, b);
+      } else {
+        sc = sum_rows(part[0]);
+      }
+      const int tok = s * 16 + col;
+      if (owner && tok < nv_cur) out_row[static_cast<int64_t>(pi) * kGroup + tok] = sc;
+    }
+    rc_cur = rc_nxt; rp_cur = rp_nxt; nv_cur = nv_nxt;
   }
 }
 

@@ -15,6 +15,11 @@
 //     an edge (only possible on an axis or a diagonal) belongs to the upper
 //     bin, theta = +pi is clamped into the last bin, and x = y = 0 goes to
 //     bin 2^(t-1).
+// With the grouped angle quantizer (Section 3.2 as printed) the angle is instead
+//   theta = atan2(y, x) in float64,  a = Clamp(floor((theta - z_t) / s_t), 0, 2^t - 1)
+// with z_t = min, s_t = (max - min) / 2^t of theta over the group, rounded once from
+// float64 to fp16 and used as rounded (a = 0 when s_t == 0); the page's parameter block
+// then holds the 64 radius entries followed by the 64 angle entries.
 //
 // One work-group encodes one page (128 tokens) of one KV head: thread =
 // (pair octet o = tid % 8, token slot tid / 8), four tokens per thread.
@@ -92,10 +97,25 @@ __device__ __forceinline__ float max_nonneg(float p, float q) {
 // `keys` points at the head's d elements of the group's first token; rows are token_stride
 // elements apart; nv <= 128 tokens are valid.  codes_ph / params_ph are the (page, head) slices
 // of the pools.  Contains a work-group barrier: all threads must call it.
-template <int RB, int TB, typename KT>
+// LDS of encode_group: per-wavefront minima / maxima of the radii (and of the angles).
+template <bool GA>
+struct EncodeShared {
+  float mn[kEncThreads / 64][kPairs];
+  float mx[kEncThreads / 64][kPairs];
+  double tmn[GA ? kEncThreads / 64 : 1][GA ? kPairs : 1];
+  double tmx[GA ? kEncThreads / 64 : 1][GA ? kPairs : 1];
+};
+
+__device__ __forceinline__ uint32_t pack_half2(float lo, float hi) {
+  return static_cast<uint32_t>(__half_as_ushort(__float2half_rn(lo))) |
+         (static_cast<uint32_t>(__half_as_ushort(__float2half_rn(hi))) << 16);
+}
+
+template <int RB, int TB, typename KT, bool GA>
 __device__ __forceinline__ void encode_group(const KT* keys, int64_t token_stride, int nv, uint8_t* codes_ph,
-                                             uint32_t* params_ph, const double* tan_edge,
-                                             float (*s_mn)[kPairs], float (*s_mx)[kPairs]) {
+                                             uint32_t* params_ph, const double* tan_edge, EncodeShared<GA>& sh) {
+  float(*s_mn)[kPairs] = sh.mn;
+  float(*s_mx)[kPairs] = sh.mx;
   constexpr int W = RB + TB;
   constexpr int UB = 2 * W;
   const int tid = threadIdx.x;
@@ -105,9 +125,11 @@ __device__ __forceinline__ void encode_group(const KT* keys, int64_t token_strid
 
   float rho[kItems][8];
   uint32_t ang[kItems][2];        // 8 angle codes, one byte each
+  double th[GA ? kItems : 1][8];  // grouped angle quantizer: theta of every pair
   float mn[8], mx[8];
+  double tmn[8], tmx[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) { mn[e] = INFINITY; mx[e] = 0.f; }
+  for (int e = 0; e < 8; ++e) { mn[e] = INFINITY; mx[e] = 0.f; tmn[e] = 4.0; tmx[e] = -4.0; }
 
   const KT* base = keys + o * 8;
 #pragma unroll
@@ -127,7 +149,14 @@ __device__ __forceinline__ void encode_group(const KT* keys, int64_t token_strid
         rho[it][e] = r;
         mn[e] = min_nonneg(mn[e], r);
         mx[e] = max_nonneg(mx[e], r);
-        ang[it][e >> 2] |= angle_bin<TB>(x[e], y[e], tan_edge) << (8 * (e & 3));
+        if constexpr (GA) {
+          const double t = atan2(static_cast<double>(y[e]), static_cast<double>(x[e]));
+          th[it][e] = t;
+          tmn[e] = fmin(tmn[e], t);
+          tmx[e] = fmax(tmx[e], t);
+        } else {
+          ang[it][e >> 2] |= angle_bin<TB>(x[e], y[e], tan_edge) << (8 * (e & 3));
+        }
       }
     } else {
 #pragma unroll
@@ -142,6 +171,10 @@ __device__ __forceinline__ void encode_group(const KT* keys, int64_t token_strid
     for (int m = 8; m < 64; m <<= 1) {
       mn[e] = min_nonneg(mn[e], __shfl_xor(mn[e], m));
       mx[e] = max_nonneg(mx[e], __shfl_xor(mx[e], m));
+      if constexpr (GA) {
+        tmn[e] = fmin(tmn[e], __shfl_xor(tmn[e], m));
+        tmx[e] = fmax(tmx[e], __shfl_xor(tmx[e], m));
+      }
     }
   }
   if ((tid & 63) < 8) {
@@ -149,6 +182,10 @@ __device__ __forceinline__ void encode_group(const KT* keys, int64_t token_strid
     for (int e = 0; e < 8; ++e) {
       s_mn[wave][o * 8 + e] = mn[e];
       s_mx[wave][o * 8 + e] = mx[e];
+      if constexpr (GA) {
+        sh.tmn[wave][o * 8 + e] = tmn[e];
+        sh.tmx[wave][o * 8 + e] = tmx[e];
+      }
     }
   }
   __syncthreads();
@@ -175,6 +212,28 @@ __device__ __forceinline__ void encode_group(const KT* keys, int64_t token_strid
     dst[0] = make_uint4(packed_params[0], packed_params[1], packed_params[2], packed_params[3]);
     dst[1] = make_uint4(packed_params[4], packed_params[5], packed_params[6], packed_params[7]);
   }
+  // grouped angle quantizer: (s_t, z_t) of this thread's 8 pairs, as stored
+  double ts[8], tz[8];
+  if constexpr (GA) {
+    uint32_t packed_t[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      double lo = sh.tmn[0][o * 8 + e], hi = sh.tmx[0][o * 8 + e];
+#pragma unroll
+      for (int w = 1; w < kEncThreads / 64; ++w) {
+        lo = fmin(lo, sh.tmn[w][o * 8 + e]);
+        hi = fmax(hi, sh.tmx[w][o * 8 + e]);
+      }
+      ts[e] = round_to_half((hi - lo) * (1.0 / static_cast<double>(1 << TB)));   // exact scaling by 2^-t
+      tz[e] = round_to_half(lo);
+      packed_t[e] = pack_half2(static_cast<float>(ts[e]), static_cast<float>(tz[e]));   // exact conversions
+    }
+    if (slot == 0) {
+      uint4* dst = reinterpret_cast<uint4*>(params_ph + kPairs + o * 8);
+      dst[0] = make_uint4(packed_t[0], packed_t[1], packed_t[2], packed_t[3]);
+      dst[1] = make_uint4(packed_t[4], packed_t[5], packed_t[6], packed_t[7]);
+    }
+  }
 
   // radius codes, symbols, and the bit string of this thread's 8 pairs (8*W bits)
   uint8_t* const cbase = codes_ph + (o >> 1) * kGroup * UB;
@@ -188,7 +247,14 @@ __device__ __forceinline__ void encode_group(const KT* keys, int64_t token_strid
         float qf = floorf((rho[it][e] - zf[e]) / sf[e]);    // IEEE division
         qf = fminf(fmaxf(qf, 0.f), static_cast<float>((1 << RB) - 1));
         qf = sf[e] != 0.f ? qf : 0.f;                       // constant group: code 0 (also drops the NaN of 0/0)
-        const uint32_t ac = (ang[it][e >> 2] >> (8 * (e & 3))) & 0xffu;
+        uint32_t ac;
+        if constexpr (GA) {
+          double u = floor((th[it][e] - tz[e]) / ts[e]);     // IEEE division
+          u = fmin(fmax(u, 0.0), static_cast<double>((1 << TB) - 1));
+          ac = ts[e] != 0.0 ? static_cast<uint32_t>(u) : 0u;  // constant group: code 0
+        } else {
+          ac = (ang[it][e >> 2] >> (8 * (e & 3))) & 0xffu;
+        }
         const uint64_t sym = (static_cast<uint64_t>(ac) << RB) | static_cast<uint32_t>(qf);
         bits |= sym << (e * W);
       }
@@ -211,19 +277,18 @@ __device__ __forceinline__ void encode_group(const KT* keys, int64_t token_strid
   }
 }
 
-template <int RB, int TB, typename KT>
+template <int RB, int TB, typename KT, bool GA>
 __global__ __launch_bounds__(kEncThreads) void pq_encode_kernel(const EncodeArgs a) {
-  __shared__ float s_mn[kEncThreads / 64][kPairs];
-  __shared__ float s_mx[kEncThreads / 64][kPairs];
+  __shared__ EncodeShared<GA> stats;
   const int grp = blockIdx.x, kvh = blockIdx.y;
   const int64_t page = a.page_ids[grp];
   if (page < 0 || page >= a.n_pool_pages) return;
   const int64_t tok0 = static_cast<int64_t>(grp) * kGroup;
   const int nv = static_cast<int>(min<int64_t>(kGroup, a.n_tokens - tok0));
   const int64_t ph = page * a.n_kv_heads + kvh;
-  encode_group<RB, TB, KT>(static_cast<const KT*>(a.keys) + tok0 * a.token_stride + kvh * a.head_stride,
-                           a.token_stride, nv, a.codes + ph * (kBlocks * kGroup * 2 * (RB + TB)),
-                           a.params + ph * kPairs, a.tan_edge, s_mn, s_mx);
+  encode_group<RB, TB, KT, GA>(static_cast<const KT*>(a.keys) + tok0 * a.token_stride + kvh * a.head_stride,
+                               a.token_stride, nv, a.codes + ph * (kBlocks * kGroup * 2 * (RB + TB)),
+                               a.params + ph * (kPairs * (GA ? 2 : 1)), a.tan_edge, stats);
 }
 
 // Appends one decode step's key per sequence to the fp16 residual buffer and, when that fills a
@@ -242,10 +307,9 @@ struct AppendArgs {
   double tan_edge[kMaxAngleBins / 8];
 };
 
-template <int RB, int TB, typename KT>
+template <int RB, int TB, typename KT, bool GA>
 __global__ __launch_bounds__(kEncThreads) void pq_append_kernel(const AppendArgs a) {
-  __shared__ float s_mn[kEncThreads / 64][kPairs];
-  __shared__ float s_mx[kEncThreads / 64][kPairs];
+  __shared__ EncodeShared<GA> stats;
   const int kvh = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x;
   const int L = a.seq_lens[seq];
   if (L < 0) return;
@@ -268,14 +332,14 @@ __global__ __launch_bounds__(kEncThreads) void pq_append_kernel(const AppendArgs
   if (page < 0 || page >= a.n_pool_pages) return;
   __syncthreads();                                // the new row is visible to the whole work-group
   const int64_t ph = page * a.n_kv_heads + kvh;
-  encode_group<RB, TB, __half>(res, kHeadDim, kGroup, a.codes + ph * (kBlocks * kGroup * 2 * (RB + TB)),
-                               a.params + ph * kPairs, a.tan_edge, s_mn, s_mx);
+  encode_group<RB, TB, __half, GA>(res, kHeadDim, kGroup, a.codes + ph * (kBlocks * kGroup * 2 * (RB + TB)),
+                                   a.params + ph * (kPairs * (GA ? 2 : 1)), a.tan_edge, stats);
 }
 
-template <int RB, int TB>
+template <int RB, int TB, bool GA = false>
 hipError_t launch_encode(const EncodeArgs& a, pq_dtype dt, dim3 grid, hipStream_t st) {
-  if (dt == PQ_F16) hipLaunchKernelGGL((pq_encode_kernel<RB, TB, __half>), grid, dim3(kEncThreads), 0, st, a);
-  else              hipLaunchKernelGGL((pq_encode_kernel<RB, TB, float>), grid, dim3(kEncThreads), 0, st, a);
+  if (dt == PQ_F16) hipLaunchKernelGGL((pq_encode_kernel<RB, TB, __half, GA>), grid, dim3(kEncThreads), 0, st, a);
+  else              hipLaunchKernelGGL((pq_encode_kernel<RB, TB, float, GA>), grid, dim3(kEncThreads), 0, st, a);
   return hipGetLastError();
 }
 
@@ -321,7 +385,9 @@ extern "C" int pq_encode_keys(const pq_layout* layout, const void* keys, pq_dtyp
   const dim3 grid(static_cast<uint32_t>(n_groups), layout->n_kv_heads);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e = hipSuccess;
-  switch (layout->r_bits * 10 + layout->t_bits) {
+  switch (layout->r_bits * 10 + layout->t_bits + (layout->angle_quantizer == PQ_ANGLE_GROUPED ? 100 : 0)) {
+    case 144: e = launch_encode<4, 4, true>(a, key_dtype, grid, st); break;
+    case 133: e = launch_encode<3, 3, true>(a, key_dtype, grid, st); break;
     case 44: e = launch_encode<4, 4>(a, key_dtype, grid, st); break;
     case 33: e = launch_encode<3, 3>(a, key_dtype, grid, st); break;
     case 53: e = launch_encode<5, 3>(a, key_dtype, grid, st); break;
@@ -336,10 +402,10 @@ extern "C" int pq_encode_keys(const pq_layout* layout, const void* keys, pq_dtyp
 
 namespace pq {
 namespace {
-template <int RB, int TB>
+template <int RB, int TB, bool GA = false>
 hipError_t launch_append(const AppendArgs& a, pq_dtype dt, dim3 grid, hipStream_t st) {
-  if (dt == PQ_F16) hipLaunchKernelGGL((pq_append_kernel<RB, TB, __half>), grid, dim3(kEncThreads), 0, st, a);
-  else              hipLaunchKernelGGL((pq_append_kernel<RB, TB, float>), grid, dim3(kEncThreads), 0, st, a);
+  if (dt == PQ_F16) hipLaunchKernelGGL((pq_append_kernel<RB, TB, __half, GA>), grid, dim3(kEncThreads), 0, st, a);
+  else              hipLaunchKernelGGL((pq_append_kernel<RB, TB, float, GA>), grid, dim3(kEncThreads), 0, st, a);
   return hipGetLastError();
 }
 }  // namespace
@@ -375,7 +441,9 @@ extern "C" int pq_append_keys(const pq_layout* layout, const void* new_keys, pq_
   const dim3 grid(layout->n_kv_heads, n_seqs);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e = hipSuccess;
-  switch (layout->r_bits * 10 + layout->t_bits) {
+  switch (layout->r_bits * 10 + layout->t_bits + (layout->angle_quantizer == PQ_ANGLE_GROUPED ? 100 : 0)) {
+    case 144: e = launch_append<4, 4, true>(a, key_dtype, grid, st); break;
+    case 133: e = launch_append<3, 3, true>(a, key_dtype, grid, st); break;
     case 44: e = launch_append<4, 4>(a, key_dtype, grid, st); break;
     case 33: e = launch_append<3, 3>(a, key_dtype, grid, st); break;
     case 53: e = launch_append<5, 3>(a, key_dtype, grid, st); break;

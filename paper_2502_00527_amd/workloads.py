@@ -52,6 +52,7 @@ class Workload:
     outlier_scale: float
     outlier_first_coord_only: bool
     shuffled_pages: bool       # page ids are a random permutation of the pool
+    grouped_angles: bool = False   # angle quantizer: per-group min/scale instead of the uniform grid
 
     @property
     def seed(self) -> int:

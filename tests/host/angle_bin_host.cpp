@@ -20,3 +20,8 @@ extern "C" int angle_bins_host(const float* x, const float* y, int64_t n, int t_
   }
   return 0;
 }
+
+// The library's float64 -> fp16-grid rounding (parameters of the grouped angle quantizer).
+extern "C" void round_to_half_host(const double* v, int64_t n, double* out) {
+  for (int64_t i = 0; i < n; ++i) out[i] = pq::round_to_half(v[i]);
+}

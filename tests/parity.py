@@ -4,7 +4,8 @@ Bars (from the task's stated tolerances):
   * radius codes, parameters, padding bytes: bit-exact
   * angle codes: bit-exact, except pairs whose angle lies within 1e-6 rad of a bin
     edge, where the cyclic neighbour bin is accepted; such mismatches are counted
-    and may be at most 1e-6 of all codes
+    and may be at most 1e-6 of all codes (grouped angle quantizer: the edges are the
+    group's own z + k s, the parameters are bit-exact like the radius ones)
   * scores: |gpu - ref| <= 1e-3 * max(|ref|, 0.01 * ||q|| * ||k~||)  (fp32 accumulate;
     the floor keeps "relative error" meaningful for scores that cancel to ~0)
   * attention output: max-abs error <= 2e-3
@@ -28,37 +29,40 @@ class OracleSeq:
     def __init__(self, wl: W.Workload, seq: int, length: int):
         self.wl, self.seq, self.length = wl, seq, length
         self.keys = W.keys_for_seq(wl, seq, length)
-        self.enc = polar.encode_keys(self.keys, wl.r_bits, wl.t_bits, wl.group_tokens)
+        self.enc = polar.encode_keys(self.keys, wl.r_bits, wl.t_bits, wl.group_tokens,
+                                     grouped_angles=wl.grouped_angles)
         self.codes, self.params = cache_format.pack_sequence(
             self.enc["a"], self.enc["c"], self.enc["scale"], self.enc["zero"], wl.r_bits, wl.t_bits,
-            wl.group_tokens)
+            wl.group_tokens, self.enc.get("t_scale"), self.enc.get("t_zero"))
 
     def attend(self, q_seq: np.ndarray, sm_scale: float):
         """(scores [Hq, L], out [Hq, d], k_hat) from the oracle's own packed bytes."""
         wl = self.wl
-        a, c, scale, zero = cache_format.unpack_pages(self.codes, self.params, self.length, wl.r_bits, wl.t_bits)
-        k_hat = polar.dequant_keys(a, c, scale, zero, wl.t_bits, wl.group_tokens)
+        a, c, *par = cache_format.unpack_pages(self.codes, self.params, self.length, wl.r_bits, wl.t_bits)
+        k_hat = polar.dequant_keys(a, c, par[0], par[1], wl.t_bits, wl.group_tokens, *par[2:])
         v = W.values_for_seq(wl, self.seq, self.length).astype(np.float64)
         scores, out = attention.attend(q_seq.astype(np.float64), k_hat, v, sm_scale)
         return scores, out, k_hat
 
 
 def compare_encoding(ref: OracleSeq, gpu_codes: np.ndarray, gpu_params: np.ndarray):
-    """gpu_codes uint8 [n_pages, H, P/16, g, 2w], gpu_params fp16 [n_pages, H, P, 2]: the
-    sequence's pages in order.  Returns (n_codes, n_edge_mismatches); raises on a real error."""
+    """gpu_codes uint8 [n_pages, H, P/16, g, 2w], gpu_params fp16 [n_pages, H, P, 2] (or
+    [n_pages, H, 2, P, 2] with grouped angles): the sequence's pages in order.
+    Returns (n_codes, n_edge_mismatches); raises on a real error."""
     wl = ref.wl
     assert gpu_codes.shape == ref.codes.shape and gpu_params.shape == ref.params.shape
     # parameters: bit patterns
     np.testing.assert_array_equal(gpu_params.view(np.uint16), ref.params.view(np.uint16),
-                                  err_msg="radius scale / zero-point bits differ")
-    a_g, c_g, _, _ = cache_format.unpack_pages(gpu_codes, gpu_params, ref.length, wl.r_bits, wl.t_bits)
+                                  err_msg="scale / zero-point bits differ")
+    a_g, c_g = cache_format.unpack_pages(gpu_codes, gpu_params, ref.length, wl.r_bits, wl.t_bits)[:2]
     np.testing.assert_array_equal(c_g, ref.enc["c"], err_msg="radius codes differ")
     diff = a_g != ref.enc["a"]
     n_bad = int(diff.sum())
     if n_bad:
         nb = 1 << wl.t_bits
         cyc = np.abs(a_g[diff] - ref.enc["a"][diff])
-        cyc = np.minimum(cyc, nb - cyc)
+        if not wl.grouped_angles:                      # the uniform grid is a circle, a group's grid is not
+            cyc = np.minimum(cyc, nb - cyc)
         assert np.all(cyc == 1), "angle code off by more than one bin"
         assert np.all(ref.enc["edge_dist"][diff] <= EDGE_RAD), \
             f"angle codes differ away from a bin edge (min dist {ref.enc['edge_dist'][diff].max():.3e} rad)"

@@ -42,6 +42,14 @@ def test_page_sizes_and_bit_accounting(lib):
     # (r+t)/2 bits per element + 16/g bits of parameters (Appendix B.1, uniform angle grid)
     bits = 8 * (pq.pq_codes_bytes_per_page(lay) + pq.pq_params_bytes_per_page(lay)) / (8 * 128 * 128)
     assert bits == 4.125
+    # grouped angle quantizer: a second (scale, zero) per pair and group, 32/g bits in all (Appendix B.1)
+    grouped = pq.Layout(128, 4, 4, 128, 8, 1)
+    assert pq.pq_params_bytes_per_page(grouped) == 2 * 8 * 64 * 4
+    assert pq.pq_codes_bytes_per_page(grouped) == pq.pq_codes_bytes_per_page(lay)
+    assert 8 * (pq.pq_codes_bytes_per_page(grouped) + pq.pq_params_bytes_per_page(grouped)) / (8 * 128 * 128) == 4.25
+    assert pq.pq_params_bytes_per_page(pq.Layout(128, 3, 3, 128, 8, 1)) == 2 * 8 * 64 * 4
+    assert pq.pq_params_bytes_per_page(pq.Layout(128, 5, 3, 128, 8, 1)) == 0     # grouped: (4,4), (3,3) only
+    assert pq.pq_params_bytes_per_page(pq.Layout(128, 4, 4, 128, 8, 2)) == 0     # unknown quantizer
     lay33 = pq.Layout(128, 3, 3, 128, 8)
     assert pq.pq_codes_bytes_per_page(lay33) == 8 * 128 * 48
     for bad in (pq.Layout(64, 4, 4, 128, 8), pq.Layout(128, 4, 3, 128, 8), pq.Layout(128, 4, 4, 64, 8),
@@ -93,4 +101,9 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert st == -1
     st = lib.pq_append_keys(ctypes.byref(lay), null, 0, 4, null, null, null, 8, null, null, 16, null)
     assert st == -1
-    assert pq.pq_version() >= 100
+    # grouped angles with quantized values: no kernel
+    grouped = pq.Layout(128, 4, 4, 128, 8, 1)
+    st = lib.pq_decode_partials(ctypes.byref(grouped), fake, 0, 1, 32, fake, fake, fake, 4, fake, 4, fake, 1, fake, 128,
+                                0.1, null, 0, null, fake, 1 << 20, null)
+    assert st == -2
+    assert pq.pq_version() >= 101

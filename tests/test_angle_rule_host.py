@@ -22,6 +22,8 @@ def host_lib(tmp_path_factory):
     lib = ctypes.CDLL(str(out))
     lib.angle_bins_host.restype = ctypes.c_int
     lib.angle_bins_host.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
+    lib.round_to_half_host.restype = None
+    lib.round_to_half_host.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
     return lib
 
 
@@ -62,3 +64,21 @@ def test_angle_rule_matches_oracle(host_lib, t):
     # the two float64 evaluations may differ only within ~1e-15 rad of an irrational edge
     assert not np.any(bad & (edge > 1e-12)), (x[bad][:5], y[bad][:5], got[bad][:5], want[bad][:5])
     assert bad.sum() <= 2
+
+
+def test_round_to_half_is_one_nearest_even_rounding(host_lib):
+    """float64 -> fp16 in one step: NumPy's float64 -> float16 cast is the reference (a detour
+    through float32 would round twice and differ on some of these inputs)."""
+    rng = np.random.default_rng(78)
+    v = np.concatenate([
+        rng.uniform(-np.pi, np.pi, 200000), rng.uniform(-0.5, 0.5, 100000), rng.standard_normal(100000) * 1e-3,
+        rng.standard_normal(50000) * 1e-6, rng.standard_normal(20000) * 1e-8, [0.0, -0.0, 6.0e-8, 2.0 ** -25, 3 * 2.0 ** -25],
+        # exact ties between neighbouring fp16 values, and values a float32 detour gets wrong
+        (np.arange(2048, 4096)[::7] + 0.5) * 2.0 ** -10, (np.arange(2048, 4096)[::7] + 0.5) * 2.0 ** -10 * (1 + 2.0 ** -40),
+        (np.arange(1, 1024)[::5] + 0.5) * 2.0 ** -24])
+    out = np.empty_like(v)
+    host_lib.round_to_half_host(v.ctypes.data, v.size, out.ctypes.data)
+    want = v.astype(np.float16).astype(np.float64)
+    assert np.array_equal(out, want)
+    twice = v.astype(np.float32).astype(np.float16).astype(np.float64)
+    assert (twice != want).any()

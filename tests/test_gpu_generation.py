@@ -21,14 +21,14 @@ def _say(msg):
     sys.stdout.flush()
 
 
-@pytest.mark.parametrize("bits", [(4, 4), (3, 3)])
+@pytest.mark.parametrize("bits", [(4, 4, False), (3, 3, False), (4, 4, True), (3, 3, True)])
 def test_append_then_decode_with_residual(bits):
     import paper_2502_00527_amd as pq
     from paper_2502_00527_amd.cache import make_layout
 
-    r, t = bits
+    r, t, grouped = bits
     wl = W.WORKLOADS["gqa"].scaled(n_seqs=3, n_q_heads=8, n_kv_heads=2, max_len=1024, min_len=1024,
-                                   r_bits=r, t_bits=t, shuffled_pages=True)
+                                   r_bits=r, t_bits=t, shuffled_pages=True, grouped_angles=grouped)
     layout = make_layout(wl)
     g, H, d, S = wl.group_tokens, wl.n_kv_heads, wl.head_dim, wl.n_seqs
     start = np.array([300, 128, 5], np.int32)
@@ -41,7 +41,8 @@ def test_append_then_decode_with_residual(bits):
     q_h = W.queries(wl)
     ub = 2 * (r + t)
     codes = torch.full((total, H, d // 32, g, ub), 0x5A, dtype=torch.uint8, device=dev)
-    params = torch.full((total, H, d // 2, 2), float("nan"), dtype=torch.float16, device=dev)
+    params = torch.full((total, H, 2, d // 2, 2) if grouped else (total, H, d // 2, 2), float("nan"),
+                        dtype=torch.float16, device=dev)
     values = torch.zeros((total, H, g, d), dtype=torch.float16, device=dev)
     residual = torch.full((S, H, g, d), float("nan"), dtype=torch.float16, device=dev)
     bt = torch.from_numpy(np.maximum(table, 0)).to(dev)
@@ -76,8 +77,9 @@ def test_append_then_decode_with_residual(bits):
             n_full = L // g
             parts = []
             if n_full:
-                enc = polar.encode_keys(keys_all[s][: n_full * g], r, t, g)
-                parts.append(polar.dequant_keys(enc["a"], enc["c"], enc["scale"], enc["zero"], t, g))
+                enc = polar.encode_keys(keys_all[s][: n_full * g], r, t, g, grouped_angles=grouped)
+                parts.append(polar.dequant_keys(enc["a"], enc["c"], enc["scale"], enc["zero"], t, g,
+                                                enc.get("t_scale"), enc.get("t_zero")))
             if L % g:
                 parts.append(keys_all[s][n_full * g: L].astype(np.float64))
             k_ref = np.concatenate(parts)
@@ -85,7 +87,7 @@ def test_append_then_decode_with_residual(bits):
             err = score_errors(scores[s, :, :L].cpu().numpy(), ref_scores, q_h[s], k_ref)
             worst_s = max(worst_s, float(err.max()))
             worst_o = max(worst_o, float(np.abs(out[s].cpu().numpy() - ref_out).max()))
-        _say(f"[generation r{r}t{t}] step {step_no}: lens {cur.tolist()} score err {worst_s:.2e} out err {worst_o:.2e}")
+        _say(f"[generation r{r}t{t}{' grouped angles' if grouped else ''}] step {step_no}: lens {cur.tolist()} score err {worst_s:.2e} out err {worst_o:.2e}")
         assert worst_s <= SCORE_REL and worst_o <= OUT_ABS
 
     check(0)
@@ -99,8 +101,9 @@ def test_append_then_decode_with_residual(bits):
     # every group completed on the way is encoded bit-exactly as the oracle encodes it
     for s in range(S):
         n_full = int(final[s]) // g
-        enc = polar.encode_keys(keys_all[s][: n_full * g], r, t, g)
-        want_codes, want_params = cache_format.pack_sequence(enc["a"], enc["c"], enc["scale"], enc["zero"], r, t, g)
+        enc = polar.encode_keys(keys_all[s][: n_full * g], r, t, g, grouped_angles=grouped)
+        want_codes, want_params = cache_format.pack_sequence(enc["a"], enc["c"], enc["scale"], enc["zero"], r, t, g,
+                                                             enc.get("t_scale"), enc.get("t_zero"))
         ids = torch.from_numpy(table[s, :n_full].astype(np.int64)).to(dev)
         np.testing.assert_array_equal(codes[ids].cpu().numpy(), want_codes)
         np.testing.assert_array_equal(params[ids].cpu().numpy().view(np.uint16), want_params.view(np.uint16))

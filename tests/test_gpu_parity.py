@@ -44,6 +44,16 @@ SMALL = {
     "group_of_six": (WL["gqa"].scaled(n_seqs=2, n_q_heads=12, n_kv_heads=2, max_len=650, min_len=650), None),   # 4 + 2
     "group_of_seven": (WL["gqa"].scaled(n_seqs=1, n_q_heads=7, n_kv_heads=1, max_len=400, min_len=400, r_bits=3, t_bits=3), None),
     "group_of_eight": (WL["gqa"].scaled(n_seqs=1, n_q_heads=16, n_kv_heads=2, max_len=520, min_len=520), None),  # 4 + 4
+    # the paper's grouped (per-group min / scale) angle quantizer
+    "grouped_angles_gqa": (WL["gqa"].scaled(n_seqs=2, n_q_heads=8, n_kv_heads=2, max_len=1000, min_len=1000,
+                                            grouped_angles=True), None),
+    "grouped_angles_tiny_fp32": (WL["tiny"].scaled(max_len=2100, min_len=2100, grouped_angles=True), None),
+    "grouped_angles_r3t3_many_chunks": (WL["long33"].scaled(n_q_heads=4, n_kv_heads=2, max_len=5001, min_len=5001,
+                                                            grouped_angles=True), None),
+    "grouped_angles_edge_lengths": (WL["gqa"].scaled(n_seqs=5, n_q_heads=6, n_kv_heads=1, max_len=300, min_len=300,
+                                                     grouped_angles=True), np.array([0, 1, 128, 129, 300], np.int32)),
+    "grouped_angles_ragged_pages": (WL["ragged"].scaled(n_seqs=6, n_q_heads=8, n_kv_heads=2, max_len=2000, min_len=1,
+                                                        grouped_angles=True), None),
 }
 
 
@@ -155,7 +165,8 @@ def test_results_are_deterministic():
 
 
 @pytest.mark.parametrize("name", ["gqa_ragged_tail", "tiny33_fp32", "group_of_two", "ragged_pages", "bits_r5t3",
-                                  "group_of_six"])
+                                  "group_of_six", "grouped_angles_gqa", "grouped_angles_edge_lengths",
+                                  "grouped_angles_r3t3_many_chunks"])
 def test_score_keys_entry_point(name):
     """pq_score_keys (the query-key product alone) against the oracle's dequantize-then-dot scores,
     and against the scores pq_decode_attention reports for the same cache."""
@@ -264,10 +275,11 @@ FULL = {
     "mha": [5],
     "long33": [0],
     "ragged": [0, 37],
+    "gqa_grouped_angles": [6],
 }
 
 
 @pytest.mark.parametrize("name", list(FULL))
 def test_full_size_sampled(name):
-    wl = WL[name]
+    wl = WL["gqa"].scaled(grouped_angles=True) if name == "gqa_grouped_angles" else WL[name]
     _check_workload(name + "_full", wl, None, sample_seqs=FULL[name])
