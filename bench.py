@@ -33,7 +33,8 @@ def algorithmic_bytes(wl, lens, v_bits: int = 16) -> int:
     plus 4 bytes of scale / zero-point per token) of every cached (KV head, token)."""
     w = wl.r_bits + wl.t_bits
     v_bytes = wl.head_dim * 2 if v_bits == 16 else wl.head_dim * v_bits // 8 + 4
-    per_token = (wl.head_dim // 2) * w // 8 + (wl.head_dim // 2) * 4 / wl.group_tokens + v_bytes
+    param_sets = 2 if wl.grouped_angles else 1      # radius (and angle) scale / zero-point per pair and group
+    per_token = (wl.head_dim // 2) * w // 8 + (wl.head_dim // 2) * 4 * param_sets / wl.group_tokens + v_bytes
     return int(round(float(lens.astype("int64").sum()) * wl.n_kv_heads * per_token))
 
 
@@ -67,9 +68,9 @@ def cpu_baseline(wl, lens, budget_s: float = 20.0):
         for s in range(wl.n_seqs):
             L = int(lens[s])
             keys = W.keys_for_seq(wl, s, L)
-            enc = polar.encode_keys(keys, wl.r_bits, wl.t_bits, g)                 # not timed: prefill
+            enc = polar.encode_keys(keys, wl.r_bits, wl.t_bits, g, grouped_angles=wl.grouped_angles)   # not timed: prefill
             codes, params = cache_format.pack_sequence(enc["a"], enc["c"], enc["scale"], enc["zero"],
-                                                       wl.r_bits, wl.t_bits, g)
+                                                       wl.r_bits, wl.t_bits, g, enc.get("t_scale"), enc.get("t_zero"))
             n_pages = codes.shape[0]
             vals = np.zeros((n_pages * g, wl.n_kv_heads, wl.head_dim), np.float16)
             vals[:L] = W.values_for_seq(wl, s, L)
@@ -110,6 +111,8 @@ def main() -> int:
     ap.add_argument("--workload", default="gqa", choices=["gqa", "mha", "long33", "ragged", "tiny"])
     ap.add_argument("--v-bits", type=int, default=16, choices=[16, 4, 2],
                     help="value precision: 16 = fp16 values (the headline configuration), 4 / 2 = token-wise quantized")
+    ap.add_argument("--grouped-angles", action="store_true",
+                    help="the paper's per-group min/scale angle quantizer instead of the uniform grid (the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     args = ap.parse_args()
@@ -128,6 +131,8 @@ def main() -> int:
     pq.load_library()          # raises if libpolarquant.so is not built: there is no fallback
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     wl = W.WORKLOADS[args.workload]
+    if args.grouped_angles:
+        wl = wl.scaled(grouped_angles=True)
     t0 = time.time()
     cache = build_device_cache(wl, v_bits=args.v_bits,
                                progress=lambda s: print(f"[bench] encoded sequence {s + 1}/{wl.n_seqs}",
@@ -200,13 +205,13 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.n_seqs} seqs x {wl.n_q_heads} q heads over {wl.n_kv_heads} kv heads, "
                                f"head_dim {wl.head_dim}, context {wl.min_len}..{wl.max_len}, r{wl.r_bits}/t{wl.t_bits}, "
-                               f"group {wl.group_tokens}, {'fp16' if args.v_bits == 16 else str(args.v_bits) + '-bit'} values, "
+                               f"group {wl.group_tokens}, {'grouped' if wl.grouped_angles else 'uniform'} angle quantizer, {'fp16' if args.v_bits == 16 else str(args.v_bits) + '-bit'} values, "
                                f"RoPE base {wl.rope_base:g}",
                    "keys_scored_per_step": keys_scored,
                    "kv_tokens_per_step": int(lens.astype(np.int64).sum()) * wl.n_kv_heads},
         "roofline": {"bound": "hbm", "kernel": "pq_decode_partials_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": read_traffic_note(wl.name) if args.v_bits == 16 else None,
+                     "traffic": read_traffic_note(wl.name) if args.v_bits == 16 and not wl.grouped_angles else None,
                      "algorithmic_bytes": alg_bytes,
                      "ms_per_launch": ms_partials, "ms_merge_kernel": ms_merge,
                      "read_stream_GBps": read_stream_gbps,

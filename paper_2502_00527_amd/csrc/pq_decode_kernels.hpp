@@ -401,7 +401,10 @@ template <int TB>
 __device__ __forceinline__ void build_group_table(uint32_t lut_w, uint32_t tpar, uint32_t q_addr, int lane) {
   constexpr int NA = 1 << TB;
   const float level = static_cast<float>(lane & (NA - 1)) + 0.5f;
-#pragma unroll
+#ifndef PQ_BUILD_UNROLL
+#define PQ_BUILD_UNROLL 4          // fully unrolled, the attention kernel spills registers
+#endif
+#pragma unroll PQ_BUILD_UNROLL
   for (int it = 0; it < NA; ++it) {
     const int j = it * (64 >> TB) + (lane >> TB);
     const uint32_t p = static_cast<uint32_t>(__shfl(static_cast<int>(tpar), j));
