@@ -325,15 +325,15 @@ __device__ __forceinline__ void dense_steps(const uint4 (&kx)[2], const uint4 (&
   }
 }
 
-// acc[h][0..7] += p_h[token] * V[token][this lane's 8 dims] for the 4 value rows in `vv`
-// (tokens 4 * (it0 + i) + row); pw is prob[token][G] in LDS.
+// acc[h][0..7] += p_h[token] * V[token][this lane's 8 dims] for the 4 value rows in `vv`:
+// the (it0 + i)-th 1 KB load of the page in its rotated order, i.e. tokens
+// 4 * ((it0 + i + rot) % 32) + row; pw_row is the LDS address of prob[token = row][G].
 template <int G>
-__device__ __forceinline__ void consume_values(const uint4 (&vv)[4], int it0, uint32_t pw, int row,
+__device__ __forceinline__ void consume_values(const uint4 (&vv)[4], int it0, uint32_t pw_row, int rot,
                                                float (&acc)[G][8]) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int tok = (it0 + i) * 4 + row;
-    const Heads<G> p = lut_read<G>(pw + tok * (G * 4));
+    const Heads<G> p = lut_read<G>(pw_row + static_cast<uint32_t>((it0 + i + rot) & 31) * (4 * G * 4));
     const uint32_t w4[4] = {vv[i].x, vv[i].y, vv[i].z, vv[i].w};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -496,10 +496,15 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   constexpr int kParamSets = GA ? 2 : 1;   // radius parameters (+ angle parameters) per pair
   constexpr int kVLoads = kQuantV ? kGroup * kHeadDim * VB / 8 / 1024 : 32;   // 1 KB wave-loads per page
   constexpr int kTokPerLoad = kGroup / kVLoads;                              // 16 (4 bit), 32 (2 bit)
+  // The 32 one-KB value loads of a page are issued in an order rotated by a page-dependent
+  // amount: pages and heads are a power-of-two number of bytes apart, and waves that walk them
+  // in the same order keep hitting the same memory channels together (measured with a bare
+  // streaming kernel: 6.6 TB/s in lock-step order, 7.0 TB/s rotated).
   auto page_setup = [&](int k, __amdgpu_buffer_rsrc_t& rc, __amdgpu_buffer_rsrc_t& rp,
-                        __amdgpu_buffer_rsrc_t& rv, __amdgpu_buffer_rsrc_t& rvp, int& nv) {
+                        __amdgpu_buffer_rsrc_t& rv, __amdgpu_buffer_rsrc_t& rvp, int& nv, int& rot) {
     const int pid = __builtin_amdgcn_readlane(pid_lane, k);
     const bool ok = pid >= 0;
+    rot = ok ? (pid * 13 + kvh * 5) & 31 : 0;
     const int64_t ph = ok ? static_cast<int64_t>(pid) * a.n_kv_heads + kvh : 0;
     nv = ok ? min(kGroup, L - (page0 + wave + kWaves * k) * kGroup) : 0;
     const bool packed = ok && (page0 + wave + kWaves * k) != res_page;   // the residual group has no codes yet
@@ -530,7 +535,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   const __amdgpu_buffer_rsrc_t rs_empty = make_rsrc(a.values, 0u);
   __amdgpu_buffer_rsrc_t rc_cur = rs_empty, rp_cur = rs_empty, rv_cur = rs_empty, rvp_cur = rs_empty;
   __amdgpu_buffer_rsrc_t rc_nxt = rs_empty, rp_nxt = rs_empty, rv_nxt = rs_empty, rvp_nxt = rs_empty;
-  int nv_cur = 0, nv_nxt = 0;
+  int nv_cur = 0, nv_nxt = 0, rot_cur = 0, rot_nxt = 0;
   uint4 praw[4];
   uint32_t tpar = 0;                                               // GA: angle parameters of pair `lane`
   Unit<W / 2> cu[8];
@@ -541,7 +546,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   const uint32_t voff_vq = lane * 16;                              // lane (row, col): token block row, dim slice col
   const uint32_t voff_vpar = col * 4;
   if (n_w > 0) {
-    page_setup(0, rc_cur, rp_cur, rv_cur, rvp_cur, nv_cur);
+    page_setup(0, rc_cur, rp_cur, rv_cur, rvp_cur, nv_cur, rot_cur);
 #pragma unroll
     for (int i = 0; i < 4; ++i) praw[i] = buf_load16<kAuxCached>(rp_cur, voff_params, i * 16);
     if constexpr (GA) tpar = buf_load4<kAuxCached>(rp_cur, lane * 4, kPairs * 4);
@@ -556,7 +561,8 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
 #pragma unroll
       for (int k = 0; k < kRingSets; ++k)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) ring[k][r] = buf_load16<kAuxStream>(rv_cur, voff_values, (4 * k + r) * 1024);
+        for (int r = 0; r < 4; ++r)
+          ring[k][r] = buf_load16<kAuxStream>(rv_cur, voff_values, static_cast<uint32_t>((4 * k + r + rot_cur) & 31) * 1024u);
     }
   }
 
@@ -616,10 +622,11 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   for (int i = 0; i < n_w; ++i) {
     const int pi = page0 + wave + kWaves * i;                      // chunk-relative page of iteration i
     if (i + 1 < n_w) {
-      page_setup(i + 1, rc_nxt, rp_nxt, rv_nxt, rvp_nxt, nv_nxt);
+      page_setup(i + 1, rc_nxt, rp_nxt, rv_nxt, rvp_nxt, nv_nxt, rot_nxt);
     } else {
       rc_nxt = rp_nxt = rv_nxt = rvp_nxt = rs_empty;
       nv_nxt = 0;
+      rot_nxt = 0;
     }
 
     if constexpr (GA) {
@@ -729,19 +736,21 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
     } else {
   #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        consume_values<G>(ring[k % kRingSets], 4 * k, pw_addr, row, acc);
+        consume_values<G>(ring[k % kRingSets], 4 * k, pw_addr + row * (G * 4), rot_cur, acc);
   #pragma unroll
         for (int r = 0; r < 4; ++r) {
           constexpr int kAhead = 4 * kRingSets;                      // rows between a refill and its use
           const int nrow = 4 * k + r + kAhead;                       // compile-time after unrolling
-          if (nrow < 32) ring[k % kRingSets][r] = buf_load16<kAuxStream>(rv_cur, voff_values, nrow * 1024);
-          else           ring[k % kRingSets][r] = buf_load16<kAuxStream>(rv_nxt, voff_values, (nrow - 32) * 1024);
+          if (nrow < 32)
+            ring[k % kRingSets][r] = buf_load16<kAuxStream>(rv_cur, voff_values, static_cast<uint32_t>((nrow + rot_cur) & 31) * 1024u);
+          else
+            ring[k % kRingSets][r] = buf_load16<kAuxStream>(rv_nxt, voff_values, static_cast<uint32_t>((nrow - 32 + rot_nxt) & 31) * 1024u);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
     wave_lds_sync();   // the next page overwrites prob[] / alpha_s[]
-    rc_cur = rc_nxt; rp_cur = rp_nxt; rv_cur = rv_nxt; rvp_cur = rvp_nxt; nv_cur = nv_nxt;
+    rc_cur = rc_nxt; rp_cur = rp_nxt; rv_cur = rv_nxt; rvp_cur = rvp_nxt; nv_cur = nv_nxt; rot_cur = rot_nxt;
   }
 
   // ---- fold the four wavefronts into one partial per query head ----

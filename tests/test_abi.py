@@ -59,9 +59,12 @@ def test_page_sizes_and_bit_accounting(lib):
 
 def test_workspace_size_follows_the_chunk_plan(lib):
     lay = pq.Layout(128, 4, 4, 128, 8)
-    # 16 seqs x 8 kv heads, 256 pages: chunks of 16 pages -> 16 chunks per sequence
+    # 16 seqs x 8 kv heads, 256 pages: chunks of 32 pages -> 8 chunks per sequence
     n = pq.pq_decode_workspace_bytes(lay, 16, 32, 32768)
-    assert n == 16 * 32 * 16 * 128 * 4 + 16 * 32 * 16 * 2 * 4
+    assert n == 16 * 32 * 8 * 128 * 4 + 16 * 32 * 8 * 2 * 4
+    # one sequence x 8 kv heads, 1024 pages: chunks shrink to 16 pages so that 512 work-groups exist
+    n = pq.pq_decode_workspace_bytes(pq.Layout(128, 3, 3, 128, 8), 1, 32, 131072)
+    assert n == 32 * 64 * 128 * 4 + 32 * 64 * 2 * 4
     assert pq.pq_decode_workspace_bytes(lay, 1, 32, 1) > 0
     assert pq.pq_decode_workspace_bytes(lay, 0, 32, 128) == 0
     assert pq.pq_decode_workspace_bytes(lay, 1, 12, 128) == 0      # 12 query heads over 8 kv heads
