@@ -107,7 +107,8 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=200,
+                    help="untimed steps; the device needs ~150 launches (~35 ms) of load to reach its steady clocks")
     ap.add_argument("--workload", default="gqa", choices=["gqa", "mha", "long33", "ragged", "tiny"])
     ap.add_argument("--v-bits", type=int, default=16, choices=[16, 4, 2],
                     help="value precision: 16 = fp16 values (the headline configuration), 4 / 2 = token-wise quantized")
