@@ -184,6 +184,33 @@ def main() -> int:
               "note": "paper Table 2 (hardware not stated): PolarQuant44 at batch 8 x 32K = 1.49 s per 10K calls"}
         del scores
 
+    # the prefill-time encoder on the 32768-token x 8-head fp16 prefill of the ragged configuration
+    # (context: it runs once per prompt, not per decode step, and is no part of `value`)
+    enc = None
+    if True:
+        pre = W.WORKLOADS["prefill"].scaled(grouped_angles=wl.grouped_angles, r_bits=wl.r_bits, t_bits=wl.t_bits)
+        from paper_2502_00527_amd.cache import make_layout
+        lay = make_layout(pre)
+        n_tok = pre.max_len
+        n_pg = n_tok // pre.group_tokens
+        keys = torch.from_numpy(W.keys_for_seq(pre, 0, n_tok)).to("cuda:0")
+        e_codes = torch.empty(n_pg * pq.pq_codes_bytes_per_page(lay), dtype=torch.uint8, device="cuda:0")
+        e_params = torch.empty(n_pg * pq.pq_params_bytes_per_page(lay), dtype=torch.uint8, device="cuda:0")
+        ids = torch.arange(n_pg, dtype=torch.int32, device="cuda:0")
+
+        def encode_only():
+            pq.pq_encode_keys(lay, keys, ids, e_codes, e_params)
+
+        for _ in range(10):
+            encode_only()
+        ms_enc = time_region(encode_only, 50, torch)
+        enc_bytes = keys.numel() * keys.element_size() + e_codes.numel() + e_params.numel()
+        enc = {"entry_point": "pq_encode_keys", "tokens": n_tok, "kv_heads": pre.n_kv_heads, "ms_per_call": ms_enc,
+               "pairs_per_s": n_tok * pre.n_kv_heads * (pre.head_dim // 2) / (ms_enc * 1e-3),
+               "GBps": enc_bytes / (ms_enc * 1e-3) / 1e9, "bound": "alu",
+               "note": "exactly rounded fp32 radius chain and exact angle classification; not HBM-bound"}
+        del keys, e_codes, e_params
+
     # what this device streams with plain 128-bit loads (context for the roofline fraction)
     probe = torch.empty(2 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
     sink = torch.zeros(64, dtype=torch.int32, device="cuda:0")
@@ -222,6 +249,8 @@ def main() -> int:
     }
     if qk is not None:
         result["qk_only"] = qk
+    if enc is not None:
+        result["encode"] = enc
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, lens, args.cpu_budget)
     print(json.dumps(result), flush=True)
