@@ -283,3 +283,83 @@ FULL = {
 def test_full_size_sampled(name):
     wl = WL["gqa"].scaled(grouped_angles=True) if name == "gqa_grouped_angles" else WL[name]
     _check_workload(name + "_full", wl, None, sample_seqs=FULL[name])
+
+
+# ---- sizes near the ends of the supported range ----
+
+def test_one_million_token_sequence():
+    """A single 1 Mi-token sequence (8193 pages, 257 chunks): index arithmetic at the long end."""
+    wl = WL["gqa"].scaled(n_seqs=1, n_q_heads=4, n_kv_heads=1, max_len=(1 << 20) + 77, min_len=(1 << 20) + 77)
+    _check_workload("one_million_tokens", wl, None)
+
+
+def test_many_short_sequences():
+    """1500 sequences of 1..300 tokens (grid of 1500 x 1 chunk, most work-groups nearly empty)."""
+    wl = WL["ragged"].scaled(n_seqs=1500, n_q_heads=2, n_kv_heads=1, max_len=300, min_len=1)
+    _check_workload("many_short_sequences", wl, None, sample_seqs=list(range(0, 1500, 7)))
+
+
+# ---- streams and graphs: the library keeps no state and allocates nothing ----
+
+def test_decode_under_hip_graph_replay():
+    """pq_decode_attention captured into a HIP graph and replayed, with eager work and
+    synchronisations between the replays, reproduces the eager result bit for bit; new inputs
+    written into the captured buffers are picked up by the next replay."""
+    from paper_2502_00527_amd.cache import build_device_cache
+
+    wl = WL["gqa"].scaled(n_seqs=3, n_q_heads=8, n_kv_heads=2, max_len=2500, min_len=900)
+    cache = build_device_cache(wl)
+    eager = cache.decode().clone()
+    torch.cuda.synchronize()
+    out = torch.zeros_like(eager)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        cache.decode(out)                      # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    _say("[graph] capture")
+    with torch.cuda.graph(graph, stream=side):
+        cache.decode(out)
+    q0 = cache.q.clone()
+    for rep in range(4):
+        out.fill_(float("nan"))
+        _say(f"[graph] replay {rep}")
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep} differs from the eager result"
+        # eager work between replays, on other buffers
+        other = cache.decode()
+        torch.cuda.synchronize()
+        assert torch.equal(other, eager)
+    # a new query in the captured input buffer
+    cache.q.copy_(torch.flip(q0, dims=[0]))
+    want = cache.decode().clone()
+    torch.cuda.synchronize()
+    out.fill_(float("nan"))
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out, want) and not torch.equal(want, eager)
+    cache.q.copy_(q0)
+
+
+def test_two_streams_with_their_own_workspaces():
+    """Two decode calls in flight on two streams (separate workspaces and outputs) give what
+    each gives alone."""
+    from paper_2502_00527_amd.cache import build_device_cache
+
+    wl_a = WL["gqa"].scaled(n_seqs=4, n_q_heads=8, n_kv_heads=2, max_len=6000, min_len=3000)
+    wl_b = WL["mha"].scaled(n_seqs=3, n_q_heads=4, n_kv_heads=4, max_len=5000, min_len=5000)
+    a, b = build_device_cache(wl_a), build_device_cache(wl_b)
+    ref_a, ref_b = a.decode().clone(), b.decode().clone()
+    torch.cuda.synchronize()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    out_a, out_b = torch.zeros_like(ref_a), torch.zeros_like(ref_b)
+    for rep in range(5):
+        with torch.cuda.stream(sa):
+            a.decode(out_a)
+        with torch.cuda.stream(sb):
+            b.decode(out_b)
+        torch.cuda.synchronize()
+        assert torch.equal(out_a, ref_a) and torch.equal(out_b, ref_b)
