@@ -16,7 +16,9 @@
  *   - Every entry point returns a pq_status; argument errors are found on the
  *     host before anything is launched.  Nothing throws or aborts.
  *   - Inputs must be finite; for non-finite keys or queries the output is
- *     unspecified (but no out-of-bounds access happens).
+ *     unspecified (but no out-of-bounds access happens).  The per-group parameters
+ *     are stored as fp16 (Appendix B.1), so pair radii must stay below the fp16
+ *     maximum (65504) to be representable.
  *
  * Pairing.  A key (or query) of head_dim d is d/2 pairs; pair j is the two
  * elements (j, j + d/2) that rotate-half RoPE turns together (footnote 2 of
@@ -246,13 +248,14 @@ int pq_append_keys(const pq_layout* layout, const void* new_keys, pq_dtype key_d
  * the paper reports in Section 5.2 (query-key multiplication kernel).  Arguments as in
  * pq_decode_attention; `scores` (device fp32 [n_seqs][n_q_heads][scores_stride], scores_stride
  * >= max_seq_len) receives the scores of tokens < seq_len, other elements are left untouched.
- * No workspace is needed.  Only packed pages are scored (no residual buffer).
+ * No workspace is needed.  residual_keys as in pq_decode_attention (NULL: every group is read
+ * from the packed pages).
  */
 int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
                   int32_t n_q_heads, const void* codes_pool, const void* params_pool,
                   int64_t n_pool_pages, const int32_t* block_table, int32_t max_pages_per_seq,
                   const int32_t* seq_lens, int32_t max_seq_len, float* scores, int64_t scores_stride,
-                  void* hip_stream);
+                  const void* residual_keys, void* hip_stream);
 
 /*
  * pq_probe_read_stream -- measurement aid, not part of the method: a plain

@@ -74,7 +74,7 @@ _SIGNATURES = {
     "pq_decode_merge": (c_int, [_LP, c_int32, c_int32, c_void_p, c_int32, c_void_p, c_void_p, c_size_t,
                                 c_void_p]),
     "pq_score_keys": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_int64, c_void_p,
-                              c_int32, c_void_p, c_int32, c_void_p, c_int64, c_void_p]),
+                              c_int32, c_void_p, c_int32, c_void_p, c_int64, c_void_p, c_void_p]),
     "pq_probe_read_stream": (c_int, [c_void_p, c_size_t, c_void_p, c_void_p]),
 }
 
@@ -283,8 +283,9 @@ def pq_append_keys(layout: Layout, new_keys, residual, seq_lens, block_table, co
 
 
 def pq_score_keys(layout: Layout, q, codes_pool, params_pool, block_table, seq_lens, max_seq_len: int,
-                  scores) -> None:
-    """Raw q . k~ of every cached token; `scores` fp32 [n_seqs, n_q_heads, stride >= max_seq_len]."""
+                  scores, residual=None) -> None:
+    """Raw q . k~ of every cached token; `scores` fp32 [n_seqs, n_q_heads, stride >= max_seq_len];
+    `residual` optional fp16 [n_seqs, n_kv_heads, g, d] (the un-quantized keys of the last group)."""
     import torch
     if q.dim() != 3 or q.shape[2] != layout.head_dim:
         raise PolarQuantError("q must be [n_seqs, n_q_heads, head_dim]")
@@ -294,7 +295,8 @@ def pq_score_keys(layout: Layout, q, codes_pool, params_pool, block_table, seq_l
         _dev_ptr(codes_pool, "codes_pool"), _dev_ptr(params_pool, "params_pool"), n_pool_pages,
         _dev_ptr(block_table, "block_table", (torch.int32,)), block_table.shape[1],
         _dev_ptr(seq_lens, "seq_lens", (torch.int32,)), max_seq_len,
-        _dev_ptr(scores, "scores", (torch.float32,)), scores.shape[-1], _stream())
+        _dev_ptr(scores, "scores", (torch.float32,)), scores.shape[-1],
+        None if residual is None else _dev_ptr(residual, "residual", (torch.float16,)), _stream())
     _check(st, "pq_score_keys")
 
 

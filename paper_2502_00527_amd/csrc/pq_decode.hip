@@ -274,7 +274,7 @@ extern "C" int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_
                              int32_t n_q_heads, const void* codes_pool, const void* params_pool,
                              int64_t n_pool_pages, const int32_t* block_table, int32_t max_pages_per_seq,
                              const int32_t* seq_lens, int32_t max_seq_len, float* scores,
-                             int64_t scores_stride, void* hip_stream) {
+                             int64_t scores_stride, const void* residual_keys, void* hip_stream) {
   const int st = check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len);
   if (st != PQ_OK) return st;
   if (!q || !codes_pool || !params_pool || !block_table || !seq_lens || !scores) return PQ_ERR_INVALID_ARG;
@@ -282,9 +282,11 @@ extern "C" int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_
   if (n_pool_pages <= 0 || max_pages_per_seq <= 0 || scores_stride < max_seq_len) return PQ_ERR_INVALID_ARG;
   const int64_t need_pages = (static_cast<int64_t>(max_seq_len) + kGroup - 1) / kGroup;
   if (need_pages > max_pages_per_seq) return PQ_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(residual_keys) & 15u) return PQ_ERR_INVALID_ARG;
   const ChunkPlan plan = plan_chunks(n_seqs, layout->n_kv_heads, max_seq_len);
   DecodeArgs a = {};
   a.q = q;
+  a.residual = static_cast<const __half*>(residual_keys);
   a.codes = static_cast<const uint8_t*>(codes_pool);
   a.params = static_cast<const uint32_t*>(params_pool);
   a.block_table = block_table;

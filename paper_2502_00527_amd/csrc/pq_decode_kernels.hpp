@@ -810,7 +810,7 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
   constexpr int kLutBytes = kPairs * ROW;
   constexpr int kParamSets = GA ? 2 : 1;
   __shared__ __attribute__((aligned(16))) uint8_t lut[(GA ? kWaves : 1) * kLutBytes];   // GA: one table per wavefront
-  __shared__ __attribute__((aligned(16))) float q_lds[GA ? kHeadDim : 1][4];
+  __shared__ __attribute__((aligned(16))) float q_lds[kHeadDim][4];   // q[dim][head]: table rebuilds, residual keys
 
   const int kvh = blockIdx.x, seq = blockIdx.y, chunk = blockIdx.z;
   const int L = min(a.seq_lens[seq], a.max_seq_len);
@@ -831,6 +831,7 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
   const uint32_t voff_params = row * (kPairsPerUnit * 4);
   constexpr uint32_t kCodesBytes = kBlocks * kGroup * UB;
 
+  const int res_page = (a.residual != nullptr && (L % kGroup) != 0) ? L / kGroup : -1;
   const int n_w = npg > wave ? (npg - wave + kWaves - 1) / kWaves : 0;
   int pid_lane = -1;
   if (lane < n_w) {
@@ -842,8 +843,9 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
     const bool ok = pid >= 0;
     const int64_t ph = ok ? static_cast<int64_t>(pid) * a.n_kv_heads + kvh : 0;
     nv = ok ? min(kGroup, L - (page0 + wave + kWaves * k) * kGroup) : 0;
-    rc = make_rsrc(a.codes + ph * kCodesBytes, ok ? kCodesBytes : 0u);
-    rp = make_rsrc(a.params + ph * (kPairs * kParamSets), ok ? kPairs * 4u * kParamSets : 0u);
+    const bool packed = ok && (page0 + wave + kWaves * k) != res_page;   // the residual group has no codes yet
+    rc = make_rsrc(a.codes + ph * kCodesBytes, packed ? kCodesBytes : 0u);
+    rp = make_rsrc(a.params + ph * (kPairs * kParamSets), packed ? kPairs * 4u * kParamSets : 0u);
   };
   const __amdgpu_buffer_rsrc_t rs_empty = make_rsrc(a.codes, 0u);
   __amdgpu_buffer_rsrc_t rc_cur = rs_empty, rp_cur = rs_empty, rc_nxt = rs_empty, rp_nxt = rs_empty;
@@ -861,12 +863,11 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
   }
   {
     const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim;
-    if constexpr (GA) {
-      if (tid < kHeadDim) {
+    if (tid < kHeadDim) {
 #pragma unroll
-        for (int h = 0; h < 4; ++h) q_lds[tid][h] = h < G ? static_cast<float>(qb[h * kHeadDim + tid]) : 0.f;
-      }
-    } else {
+      for (int h = 0; h < 4; ++h) q_lds[tid][h] = h < G ? static_cast<float>(qb[h * kHeadDim + tid]) : 0.f;
+    }
+    if constexpr (!GA) {
       float* lf = reinterpret_cast<float*>(lut);
       for (int idx = tid; idx < kPairs * NA; idx += kThreads) {
         const int j = idx >> TB, s = idx & (NA - 1);
@@ -883,6 +884,34 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
   __syncthreads();
 
   float* const out_row = a.scores + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0 + my_head) * a.scores_stride;
+
+  // With a residual buffer the last, incomplete group of the sequence is fp16 keys: plain dot
+  // products, by the wavefront that owns the group's page (same lane layout and fold as below).
+  if (res_page >= page0 + wave && res_page < page0 + npg && ((res_page - page0 - wave) & (kWaves - 1)) == 0) {
+    const int nv_res = L - res_page * kGroup;
+    const __amdgpu_buffer_rsrc_t rs_res = make_rsrc(
+        a.residual + (static_cast<int64_t>(seq) * a.n_kv_heads + kvh) * (kGroup * kHeadDim),
+        static_cast<uint32_t>(nv_res) * (kHeadDim * 2));
+    const uint32_t voff_res = col * (kHeadDim * 2) + row * 32;
+    const uint32_t qs_row = lds_addr(q_lds) + row * (16 * 16);
+#pragma unroll 1
+    for (int s = 0; s < 8; ++s) {
+      uint4 kx[2], ky[2];
+      const uint32_t soff = s * 16 * kHeadDim * 2;
+      kx[0] = buf_load16<kAuxCached>(rs_res, voff_res, soff);
+      kx[1] = buf_load16<kAuxCached>(rs_res, voff_res + 16, soff);
+      ky[0] = buf_load16<kAuxCached>(rs_res, voff_res + kPairs * 2, soff);
+      ky[1] = buf_load16<kAuxCached>(rs_res, voff_res + kPairs * 2 + 16, soff);
+      float part[G];
+#pragma unroll
+      for (int h = 0; h < G; ++h) part[h] = 0.f;
+      dense_steps<G>(kx, ky, qs_row, part);
+      const float v = fold_rows<G>(part);
+      const int tok = s * 16 + col;
+      if (owner && tok < nv_res) out_row[static_cast<int64_t>(res_page) * kGroup + tok] = v;
+    }
+  }
+
   for (int i = 0; i < n_w; ++i) {
     const int pi = page0 + wave + kWaves * i;
     if (i + 1 < n_w) {
@@ -928,7 +957,7 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
         sc = sum_rows(part[0]);
       }
       const int tok = s * 16 + col;
-      if (owner && tok < nv_cur) out_row[static_cast<int64_t>(pi) * kGroup + tok] = sc;
+      if (owner && tok < nv_cur && pi != res_page) out_row[static_cast<int64_t>(pi) * kGroup + tok] = sc;
     }
     rc_cur = rc_nxt; rp_cur = rp_nxt; nv_cur = nv_nxt;
   }

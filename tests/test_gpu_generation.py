@@ -70,7 +70,12 @@ def test_append_then_decode_with_residual(bits):
     def check(step_no):
         cur = lens.cpu().numpy()
         pq.pq_decode_attention(layout, q, codes, params, values, bt, lens, max_len, sm_scale, out, ws, scores, residual)
+        qk = torch.full_like(scores, float("nan"))
+        pq.pq_score_keys(layout, q, codes, params, bt, lens, max_len, qk, residual)     # the product alone, same keys
         torch.cuda.synchronize()
+        for s in range(S):
+            assert torch.equal(qk[s, :, : int(cur[s])], scores[s, :, : int(cur[s])])
+            assert torch.isnan(qk[s, :, int(cur[s]):]).all()
         worst_s = worst_o = 0.0
         for s in range(S):
             L = int(cur[s])
