@@ -133,6 +133,7 @@ int check_decode_shape(const pq_layout* l, int32_t n_seqs, int32_t n_q_heads, in
   const int G = n_q_heads / l->n_kv_heads;
   if (G > 16) return PQ_ERR_UNSUPPORTED;   // groups are processed 4, 2 or 1 query heads per pass
   if (n_seqs > 65535 || n_q_heads > 65535) return PQ_ERR_UNSUPPORTED;   // grid.y, merge grid.x
+  if (plan_chunks(n_seqs, l->n_kv_heads, max_seq_len).n_chunks > 65535) return PQ_ERR_UNSUPPORTED;   // grid.z
   return PQ_OK;
 }
 

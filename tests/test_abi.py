@@ -70,6 +70,9 @@ def test_workspace_size_follows_the_chunk_plan(lib):
     assert pq.pq_decode_workspace_bytes(lay, 1, 12, 128) == 0      # 12 query heads over 8 kv heads
     assert pq.pq_decode_workspace_bytes(lay, 1, 64, 128) > 0       # group of 8: two passes of 4
     assert pq.pq_decode_workspace_bytes(lay, 1, 8 * 17, 128) == 0  # group of 17 not served
+    # the chunk count is a grid dimension: 2^31 - 1 tokens would need more than 65535 chunks of 32 pages
+    assert pq.pq_decode_workspace_bytes(lay, 64, 32, 2 ** 31 - 1) == 0
+    assert pq.pq_decode_workspace_bytes(lay, 64, 32, 65535 * 32 * 128) > 0
 
 
 def test_argument_errors_are_reported_before_any_launch(lib):
