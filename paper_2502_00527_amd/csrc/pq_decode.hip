@@ -7,35 +7,46 @@ namespace pq {
 namespace {
 
 // out[seq][head][:] = sum_c 2^(m_c - M) acc_c / sum_c 2^(m_c - M) l_c over the chunks the
-// sequence really has.  One work-group of 128 threads per (head, seq): thread = (chunk slice
-// tid / 32, dims 4 * (tid % 32) ..+3); the four slices take chunks c = slice, slice + 4, ...
-// with independent 128-bit loads and are folded through LDS.
-__global__ __launch_bounds__(kHeadDim) void pq_decode_merge_kernel(
+// sequence really has.  One work-group of 256 threads per (head, seq).  The maximum M is found
+// with one (m, l) pair per thread and a shuffle / LDS reduction; then thread = (chunk slice
+// tid / 32, dims 4 * (tid % 32) ..+3) and the eight slices take chunks c = slice, slice + 8, ...
+// with independent 128-bit loads before they are folded through LDS.
+constexpr int kMergeThreads = 256;
+constexpr int kMergeSlices = kMergeThreads / 32;
+
+__global__ __launch_bounds__(kMergeThreads) void pq_decode_merge_kernel(
     const float* __restrict__ ws_acc, const float* __restrict__ ws_ml,
     const int32_t* __restrict__ seq_lens, float* __restrict__ out, int32_t n_q_heads,
     int32_t max_seq_len, int32_t pages_per_chunk, int32_t n_chunks) {
-  __shared__ float4 part_o[4][32];
-  __shared__ float part_l[4];
+  __shared__ float4 part_o[kMergeSlices][32];
+  __shared__ float part_l[kMergeSlices];
+  __shared__ float wave_max[kMergeThreads / 64];
   const int head = blockIdx.x, seq = blockIdx.y, tid = threadIdx.x;
   const int slice = tid >> 5, quad = tid & 31;
   const int L = min(seq_lens[seq], max_seq_len);
   const int64_t oh = static_cast<int64_t>(seq) * n_q_heads + head;
   if (L <= 0) {
-    out[oh * kHeadDim + tid] = 0.f;
+    if (tid < kHeadDim) out[oh * kHeadDim + tid] = 0.f;
     return;
   }
   const int n_pages = (L + kGroup - 1) / kGroup;
   const int nc = (n_pages + pages_per_chunk - 1) / pages_per_chunk;
   const float2* ml = reinterpret_cast<const float2*>(ws_ml) + oh * n_chunks;
   const float4* ac = reinterpret_cast<const float4*>(ws_acc + oh * n_chunks * kHeadDim) + quad;
-  float M = kNegInf;
-#pragma unroll 4
-  for (int c = 0; c < nc; ++c) M = fmaxf(M, ml[c].x);
+
+  float m = kNegInf;
+  for (int c = tid; c < nc; c += kMergeThreads) m = fmaxf(m, ml[c].x);
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d));
+  if ((tid & 63) == 0) wave_max[tid >> 6] = m;
+  __syncthreads();
+  const float M = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
+
   float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
   float l = 0.f;
   if (M > kNegInf) {
 #pragma unroll 4
-    for (int c = slice; c < nc; c += 4) {
+    for (int c = slice; c < nc; c += kMergeSlices) {
       const float2 mlc = ml[c];
       const float4 v = ac[static_cast<int64_t>(c) * (kHeadDim / 4)];
       const float w = __builtin_amdgcn_exp2f(mlc.x - M);
@@ -50,12 +61,13 @@ __global__ __launch_bounds__(kHeadDim) void pq_decode_merge_kernel(
   if (quad == 0) part_l[slice] = l;
   __syncthreads();
   if (slice == 0) {
-    const float lt = part_l[0] + part_l[1] + part_l[2] + part_l[3];
-    float4 r = part_o[0][quad];
+    float lt = 0.f;
+    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-    for (int s2 = 1; s2 < 4; ++s2) {
+    for (int s2 = 0; s2 < kMergeSlices; ++s2) {
       const float4 t = part_o[s2][quad];
       r.x += t.x; r.y += t.y; r.z += t.z; r.w += t.w;
+      lt += part_l[s2];
     }
     const float inv = lt > 0.f ? 1.f / lt : 0.f;
     reinterpret_cast<float4*>(out + oh * kHeadDim)[quad] = make_float4(r.x * inv, r.y * inv, r.z * inv, r.w * inv);
@@ -245,7 +257,7 @@ extern "C" int pq_decode_merge(const pq_layout* layout, int32_t n_seqs, int32_t 
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return PQ_ERR_WORKSPACE;
   const Workspace ws = carve_workspace(const_cast<void*>(workspace), n_seqs, n_q_heads, plan.n_chunks);
   if (workspace_bytes < ws.bytes) return PQ_ERR_WORKSPACE;
-  hipLaunchKernelGGL(pq_decode_merge_kernel, dim3(n_q_heads, n_seqs), dim3(kHeadDim), 0,
+  hipLaunchKernelGGL(pq_decode_merge_kernel, dim3(n_q_heads, n_seqs), dim3(kMergeThreads), 0,
                      static_cast<hipStream_t>(hip_stream), ws.acc, ws.ml, seq_lens, out, n_q_heads,
                      max_seq_len, plan.pages_per_chunk, plan.n_chunks);
   const hipError_t e = hipGetLastError();
