@@ -224,8 +224,8 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
     const int G = left >= 4 ? 4 : (left >= 2 ? 2 : 1);
     a.head0 = head0;
     if (layout->angle_quantizer == PQ_ANGLE_GROUPED) {
-      if (v_bits != 16) return PQ_ERR_UNSUPPORTED;                // grouped angles: fp16 values only
-      e = launch_partials_ga(rt, G, a, q_dtype, grid, stream);
+      e = v_bits == 16 ? launch_partials_ga(rt, G, a, q_dtype, grid, stream)
+                       : launch_partials_ga_vq(rt, G, v_bits, a, q_dtype, grid, stream);
       if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;
     } else if (v_bits != 16) {
       e = launch_partials_vq(rt, G, v_bits, a, q_dtype, grid, stream);

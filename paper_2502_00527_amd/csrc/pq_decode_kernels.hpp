@@ -82,6 +82,9 @@ hipError_t launch_partials_vq(int rt, int G, int v_bits, const DecodeArgs& a, pq
 // (4,4) or (3,3)); defined in pq_decode_ga.hip.  hipErrorInvalidValue if there is no kernel.
 hipError_t launch_partials_ga(int rt, int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st);
 hipError_t launch_scores_ga(int rt, int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st);
+// Grouped angle quantizer with quantized values; defined in pq_decode_ga_vq.hip.
+hipError_t launch_partials_ga_vq(int rt, int G, int v_bits, const DecodeArgs& a, pq_dtype qdt, dim3 grid,
+                                 hipStream_t st);
 
 namespace {
 
@@ -136,8 +139,9 @@ __device__ __forceinline__ void wave_lds_sync() {
 }
 
 // Tuning constants of the attention kernel (measured on MI355X): 4 quads of 4 value rows in
-// flight per wavefront (8 or 32 rows change nothing), and a register budget of 2 wavefronts
-// per SIMD -- 3 or 4 only fit with spills and run 1.5-2x slower.
+// flight per wavefront (8 rows in flight measure the same, 4 rows 4 % slower; the number of
+// quads must divide the 8 quads of a page), and a register budget of 2 wavefronts per SIMD --
+// with 4 query heads a third wavefront only fits with spills and runs 10-30 % slower.
 #ifndef PQ_RING_SETS
 #define PQ_RING_SETS 4
 #endif

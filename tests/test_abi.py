@@ -107,9 +107,9 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert st == -1
     st = lib.pq_append_keys(ctypes.byref(lay), null, 0, 4, null, null, null, 8, null, null, 16, null)
     assert st == -1
-    # grouped angles with quantized values: no kernel
-    grouped = pq.Layout(128, 4, 4, 128, 8, 1)
-    st = lib.pq_decode_partials(ctypes.byref(grouped), fake, 0, 1, 32, fake, fake, fake, 4, fake, 4, fake, 1, fake, 128,
+    # grouped angles exist for (4,4) and (3,3) only
+    grouped = pq.Layout(128, 5, 3, 128, 8, 1)
+    st = lib.pq_decode_partials(ctypes.byref(grouped), fake, 0, 1, 32, fake, fake, fake, 16, null, 4, fake, 1, fake, 128,
                                 0.1, null, 0, null, fake, 1 << 20, null)
     assert st == -2
     assert pq.pq_version() >= 101

@@ -198,7 +198,8 @@ def test_score_keys_entry_point(name):
 
 @pytest.mark.parametrize("case", [("gqa_ragged_tail", 4), ("gqa_ragged_tail", 2), ("tiny_full_config", 4),
                                   ("long33", 2), ("group_of_two", 4), ("edge_lengths", 4), ("ragged_pages", 2),
-                                  ("group_of_seven", 4)])
+                                  ("group_of_seven", 4), ("grouped_angles_gqa", 4), ("grouped_angles_r3t3_many_chunks", 2),
+                                  ("grouped_angles_edge_lengths", 2)])
 def test_quantized_values(case):
     """Token-wise 4/2-bit values: pq_encode_values bit-exact against the oracle's quantizer and
     packer; decode attention over them within the output bar of the oracle's attention over the
