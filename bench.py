@@ -114,6 +114,9 @@ def main() -> int:
                     help="value precision: 16 = fp16 values (the headline configuration), 4 / 2 = token-wise quantized")
     ap.add_argument("--grouped-angles", action="store_true",
                     help="the paper's per-group min/scale angle quantizer instead of the uniform grid (the headline)")
+    ap.add_argument("--copies", type=int, default=4,
+                    help="independent copies of the packed cache that successive steps rotate over, so that the "
+                         "256 MB memory-side cache cannot serve a step from the previous step's reads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     args = ap.parse_args()
@@ -143,13 +146,32 @@ def main() -> int:
     lens = cache.lens
     out = torch.empty((wl.n_seqs, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device="cuda:0")
 
+    # N copies of the pools in one N-times larger pool; copy k is reached through block table k
+    n_copies = max(1, args.copies)
+    if n_copies > 1:
+        import dataclasses
+        rep = lambda t: None if t is None else torch.cat([t] * n_copies, dim=0)
+        big = dataclasses.replace(cache, codes=rep(cache.codes), params=rep(cache.params), values=rep(cache.values),
+                                  v_params=rep(cache.v_params), n_pool_pages=cache.n_pool_pages * n_copies)
+        views = [dataclasses.replace(big, block_table=cache.block_table + k * cache.n_pool_pages)
+                 for k in range(n_copies)]
+        del big
+    else:
+        views = [cache]
+    turn = [0]
+
+    def next_view():
+        turn[0] = (turn[0] + 1) % n_copies
+        return views[turn[0]]
+
     def step():
-        cache.decode(out)
+        next_view().decode(out)
 
     def partials_only():
-        pq.pq_decode_partials(cache.layout, cache.q, cache.codes, cache.params, cache.values, cache.block_table,
-                              cache.seq_lens, cache.max_seq_len, cache.sm_scale, cache.workspace,
-                              v_bits=cache.v_bits, v_params=cache.v_params)
+        c = next_view()
+        pq.pq_decode_partials(c.layout, c.q, c.codes, c.params, c.values, c.block_table,
+                              c.seq_lens, c.max_seq_len, c.sm_scale, c.workspace,
+                              v_bits=c.v_bits, v_params=c.v_params)
 
     def merge_only():
         pq.pq_decode_merge(cache.layout, wl.n_seqs, wl.n_q_heads, cache.seq_lens, cache.max_seq_len, out,
@@ -235,6 +257,7 @@ def main() -> int:
                                f"head_dim {wl.head_dim}, context {wl.min_len}..{wl.max_len}, r{wl.r_bits}/t{wl.t_bits}, "
                                f"group {wl.group_tokens}, {'grouped' if wl.grouped_angles else 'uniform'} angle quantizer, {'fp16' if args.v_bits == 16 else str(args.v_bits) + '-bit'} values, "
                                f"RoPE base {wl.rope_base:g}",
+                   "cache_copies_rotated": n_copies,
                    "keys_scored_per_step": keys_scored,
                    "kv_tokens_per_step": int(lens.astype(np.int64).sum()) * wl.n_kv_heads},
         "roofline": {"bound": "hbm", "kernel": "pq_decode_partials_kernel", "achieved": achieved,
