@@ -176,7 +176,8 @@ int pq_encode_values(const pq_layout* layout, int32_t v_bits, const void* values
  *   v_pool, v_bits, v_params_pool
  *                 v_bits 16: v_pool is the fp16 value pool, v_params_pool is ignored (NULL);
  *                 v_bits 4 or 2: v_pool is the quantized value pool and v_params_pool its
- *                 parameter pool (built for (r_bits, t_bits) = (4,4) and (3,3))
+ *                 parameter pool (built for (r_bits, t_bits) = (4,4) and (3,3), either angle
+ *                 quantizer)
  *   n_pool_pages  pool size in pages; a block-table entry outside [0, n_pool_pages)
  *                 makes that page count as masked (no read happens)
  *   sm_scale      softmax scale (1/sqrt(d) for standard attention)
@@ -209,7 +210,9 @@ int pq_decode_attention(const pq_layout* layout, const void* q, pq_dtype q_dtype
  * every (sequence, KV head, chunk of pages) work-group writes its softmax
  * partial (running maximum, denominator, un-normalised output) into the
  * workspace.  pq_decode_merge combines the chunks of each (sequence, query
- * head) into `out`.  Arguments as in pq_decode_attention.
+ * head) into `out`.  Arguments as in pq_decode_attention; the merge must be given the same
+ * layout, n_seqs, n_q_heads, seq_lens, max_seq_len and workspace as the partials call it follows
+ * (they fix how the sequences were cut into chunks).
  */
 int pq_decode_partials(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
                        int32_t n_q_heads, const void* codes_pool, const void* params_pool,
