@@ -117,6 +117,8 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=4,
                     help="independent copies of the packed cache that successive steps rotate over, so that the "
                          "256 MB memory-side cache cannot serve a step from the previous step's reads")
+    ap.add_argument("--no-seq-order", action="store_true",
+                    help="ragged batches: do not pass the longest-first start order to the decode call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     args = ap.parse_args()
@@ -145,6 +147,11 @@ def main() -> int:
     print(f"[bench] inputs ready in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
     lens = cache.lens
     out = torch.empty((wl.n_seqs, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device="cuda:0")
+    if wl.min_len != wl.max_len and not args.no_seq_order:
+        # ragged batch: start the longest sequences first.  The order is computed once, outside the
+        # timed region: a decode step lengthens every sequence by one token, which keeps it valid.
+        cache.seq_order = torch.empty(wl.n_seqs, dtype=torch.int32, device="cuda:0")
+        pq.pq_order_sequences(cache.seq_lens, cache.seq_order)
 
     # N copies of the pools in one N-times larger pool; copy k is reached through block table k
     n_copies = max(1, args.copies)
@@ -171,7 +178,7 @@ def main() -> int:
         c = next_view()
         pq.pq_decode_partials(c.layout, c.q, c.codes, c.params, c.values, c.block_table,
                               c.seq_lens, c.max_seq_len, c.sm_scale, c.workspace,
-                              v_bits=c.v_bits, v_params=c.v_params)
+                              v_bits=c.v_bits, v_params=c.v_params, seq_order=c.seq_order)
 
     def merge_only():
         pq.pq_decode_merge(cache.layout, wl.n_seqs, wl.n_q_heads, cache.seq_lens, cache.max_seq_len, out,
@@ -257,7 +264,7 @@ def main() -> int:
                                f"head_dim {wl.head_dim}, context {wl.min_len}..{wl.max_len}, r{wl.r_bits}/t{wl.t_bits}, "
                                f"group {wl.group_tokens}, {'grouped' if wl.grouped_angles else 'uniform'} angle quantizer, {'fp16' if args.v_bits == 16 else str(args.v_bits) + '-bit'} values, "
                                f"RoPE base {wl.rope_base:g}",
-                   "cache_copies_rotated": n_copies,
+                   "cache_copies_rotated": n_copies, "longest_first_order": cache.seq_order is not None,
                    "keys_scored_per_step": keys_scored,
                    "kv_tokens_per_step": int(lens.astype(np.int64).sum()) * wl.n_kv_heads},
         "roofline": {"bound": "hbm", "kernel": "pq_decode_partials_kernel", "achieved": achieved,

@@ -23,7 +23,7 @@ __all__ = [
     "pq_values_bytes_per_page", "pq_decode_workspace_bytes", "pq_encode_keys",
     "pq_decode_attention", "pq_decode_partials", "pq_decode_merge", "pq_score_keys", "pq_append_keys",
     "pq_vq_bytes_per_page", "pq_vq_params_bytes_per_page", "pq_encode_values",
-    "pq_probe_read_stream",
+    "pq_probe_read_stream", "pq_order_sequences",
 ]
 
 PQ_F16, PQ_F32 = 0, 1
@@ -61,10 +61,10 @@ _SIGNATURES = {
                                c_void_p, c_int64, c_void_p]),
     "pq_decode_attention": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                     c_int32, c_void_p, c_int64, c_void_p, c_int32, c_void_p, c_int32, c_float, c_void_p,
-                                    c_void_p, c_int64, c_void_p, c_void_p, c_size_t, c_void_p]),
+                                    c_void_p, c_int64, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "pq_decode_partials": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                    c_int32, c_void_p, c_int64, c_void_p, c_int32, c_void_p, c_int32, c_float, c_void_p,
-                                   c_int64, c_void_p, c_void_p, c_size_t, c_void_p]),
+                                   c_int64, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "pq_vq_bytes_per_page": (c_size_t, [_LP, c_int32]),
     "pq_vq_params_bytes_per_page": (c_size_t, [_LP]),
     "pq_encode_values": (c_int, [_LP, c_int32, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p,
@@ -75,6 +75,7 @@ _SIGNATURES = {
                                 c_void_p]),
     "pq_score_keys": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_int64, c_void_p,
                               c_int32, c_void_p, c_int32, c_void_p, c_int64, c_void_p, c_void_p]),
+    "pq_order_sequences": (c_int, [c_void_p, c_int32, c_void_p, c_void_p]),
     "pq_probe_read_stream": (c_int, [c_void_p, c_size_t, c_void_p, c_void_p]),
 }
 
@@ -178,6 +179,25 @@ def pq_encode_keys(layout: Layout, keys, page_ids, codes_pool, params_pool) -> N
     _check(st, "pq_encode_keys")
 
 
+def _order_ptr(seq_order, n_seqs):
+    import torch
+    if seq_order is None:
+        return None
+    if seq_order.numel() != n_seqs:
+        raise PolarQuantError("seq_order must have one entry per sequence")
+    return _dev_ptr(seq_order, "seq_order", (torch.int32,))
+
+
+def pq_order_sequences(seq_lens, order_out) -> None:
+    """order_out (int32 [n_seqs], device) := sequence indices by decreasing length."""
+    import torch
+    if order_out.numel() != seq_lens.numel():
+        raise PolarQuantError("order_out must have one entry per sequence")
+    st = load_library().pq_order_sequences(_dev_ptr(seq_lens, "seq_lens", (torch.int32,)), seq_lens.numel(),
+                                           _dev_ptr(order_out, "order_out", (torch.int32,)), _stream())
+    _check(st, "pq_order_sequences")
+
+
 def _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens, v_bits=16, v_params=None):
     import torch
     if q.dim() != 3 or q.shape[2] != layout.head_dim:
@@ -201,7 +221,7 @@ def _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_
 
 def pq_decode_attention(layout: Layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens,
                         max_seq_len: int, sm_scale: float, out, workspace, scores=None, residual=None,
-                        v_bits: int = 16, v_params=None) -> None:
+                        v_bits: int = 16, v_params=None, seq_order=None) -> None:
     """One decode step per sequence; see include/polarquant.h.  `out` fp32 [n_seqs, n_q_heads, d];
     `scores` optional fp32 [n_seqs, n_q_heads, stride >= max_seq_len]; `workspace` a uint8 device
     tensor of at least pq_decode_workspace_bytes(...) bytes."""
@@ -214,13 +234,14 @@ def pq_decode_attention(layout: Layout, q, codes_pool, params_pool, v_pool, bloc
         None if scores is None else _dev_ptr(scores, "scores", (torch.float32,)),
         0 if scores is None else scores.shape[-1],
         None if residual is None else _dev_ptr(residual, "residual", (torch.float16,)),
+        _order_ptr(seq_order, c["n_seqs"]),
         _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream())
     _check(st, "pq_decode_attention")
 
 
 def pq_decode_partials(layout: Layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens,
                        max_seq_len: int, sm_scale: float, workspace, scores=None, residual=None,
-                       v_bits: int = 16, v_params=None) -> None:
+                       v_bits: int = 16, v_params=None, seq_order=None) -> None:
     import torch
     c = _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens, v_bits, v_params)
     st = load_library().pq_decode_partials(
@@ -229,6 +250,7 @@ def pq_decode_partials(layout: Layout, q, codes_pool, params_pool, v_pool, block
         None if scores is None else _dev_ptr(scores, "scores", (torch.float32,)),
         0 if scores is None else scores.shape[-1],
         None if residual is None else _dev_ptr(residual, "residual", (torch.float16,)),
+        _order_ptr(seq_order, c["n_seqs"]),
         _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream())
     _check(st, "pq_decode_partials")
 

@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void pq_read_stream_kernel(const uint4* __rest
 
 using namespace pq;
 
-extern "C" int pq_version(void) { return 101; }
+extern "C" int pq_version(void) { return 102; }
 
 extern "C" const char* pq_strerror(int status) {
   switch (status) {

@@ -74,6 +74,29 @@ __global__ __launch_bounds__(kMergeThreads) void pq_decode_merge_kernel(
   }
 }
 
+// order[rank] = index of the sequence with `rank` longer ones before it (ties: lower index first).
+// One work-group; every thread ranks the sequences t, t + 1024, ... against all lengths in LDS.
+constexpr int kOrderMax = 2048;
+__global__ __launch_bounds__(1024) void pq_order_kernel(const int32_t* __restrict__ seq_lens, int32_t n_seqs,
+                                                        int32_t* __restrict__ order) {
+  __shared__ int32_t len_s[kOrderMax];
+  for (int i = threadIdx.x; i < n_seqs; i += blockDim.x) {
+    if (n_seqs > kOrderMax) order[i] = i;
+    else len_s[i] = seq_lens[i];
+  }
+  if (n_seqs > kOrderMax) return;
+  __syncthreads();
+  for (int i = threadIdx.x; i < n_seqs; i += blockDim.x) {
+    const int32_t mine = len_s[i];
+    int rank = 0;
+    for (int j = 0; j < n_seqs; ++j) {
+      const int32_t other = len_s[j];
+      rank += (other > mine) || (other == mine && j < i);
+    }
+    order[rank] = i;
+  }
+}
+
 template <int RB, int TB>
 hipError_t launch_scores(int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st) {
 #define PQ_LAUNCH_SCORES(GG)                                                                            \
@@ -168,8 +191,8 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
                                   int64_t n_pool_pages, const int32_t* block_table,
                                   int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
                                   float sm_scale, float* scores, int64_t scores_stride,
-                                  const void* residual_keys, void* workspace, size_t workspace_bytes,
-                                  void* hip_stream) {
+                                  const void* residual_keys, const int32_t* seq_order, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
   const int st = check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len);
   if (st != PQ_OK) return st;
   if (!q || !codes_pool || !params_pool || !v_pool || !block_table || !seq_lens) return PQ_ERR_INVALID_ARG;
@@ -197,6 +220,8 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
   a.v_params = static_cast<const uint32_t*>(v_params_pool);
   a.block_table = block_table;
   a.seq_lens = seq_lens;
+  a.seq_order = seq_order;
+  a.n_seqs = n_seqs;
   a.scores = scores;
   a.ws_acc = ws.acc;
   a.ws_ml = ws.ml;
@@ -247,6 +272,17 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
   return PQ_OK;
 }
 
+extern "C" int pq_order_sequences(const int32_t* seq_lens, int32_t n_seqs, int32_t* order_out, void* hip_stream) {
+  if (n_seqs < 0) return PQ_ERR_INVALID_ARG;
+  if (n_seqs == 0) return PQ_OK;
+  if (!seq_lens || !order_out) return PQ_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(pq_order_kernel, dim3(1), dim3(1024), 0, static_cast<hipStream_t>(hip_stream), seq_lens,
+                     n_seqs, order_out);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return record_hip_error(e);
+  return PQ_OK;
+}
+
 extern "C" int pq_decode_merge(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
                                const int32_t* seq_lens, int32_t max_seq_len, float* out,
                                const void* workspace, size_t workspace_bytes, void* hip_stream) {
@@ -271,13 +307,13 @@ extern "C" int pq_decode_attention(const pq_layout* layout, const void* q, pq_dt
                                    int64_t n_pool_pages, const int32_t* block_table,
                                    int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
                                    float sm_scale, float* out, float* scores, int64_t scores_stride,
-                                   const void* residual_keys, void* workspace, size_t workspace_bytes,
-                                   void* hip_stream) {
+                                   const void* residual_keys, const int32_t* seq_order, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream) {
   if (!out) return PQ_ERR_INVALID_ARG;
   const int st = pq_decode_partials(layout, q, q_dtype, n_seqs, n_q_heads, codes_pool, params_pool, v_pool,
                                     v_bits, v_params_pool, n_pool_pages, block_table, max_pages_per_seq, seq_lens, max_seq_len,
-                                    sm_scale, scores, scores_stride, residual_keys, workspace, workspace_bytes,
-                                    hip_stream);
+                                    sm_scale, scores, scores_stride, residual_keys, seq_order, workspace,
+                                    workspace_bytes, hip_stream);
   if (st != PQ_OK) return st;
   return pq_decode_merge(layout, n_seqs, n_q_heads, seq_lens, max_seq_len, out, workspace, workspace_bytes,
                          hip_stream);
@@ -304,6 +340,7 @@ extern "C" int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_
   a.params = static_cast<const uint32_t*>(params_pool);
   a.block_table = block_table;
   a.seq_lens = seq_lens;
+  a.n_seqs = n_seqs;
   a.scores = scores;
   a.scores_stride = scores_stride;
   a.n_pool_pages = n_pool_pages;

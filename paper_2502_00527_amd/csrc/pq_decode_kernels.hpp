@@ -55,6 +55,8 @@ struct DecodeArgs {
   const __half* residual;   // [seq][kv_head][g][d] un-quantized keys of the last, incomplete group (or null)
   const int32_t* block_table;
   const int32_t* seq_lens;
+  const int32_t* seq_order;  // optional: sequence handled by grid row y (null: y itself)
+  int32_t n_seqs;
   float* scores;
   float* ws_acc;            // [seq][q_head][chunk][128]
   float* ws_ml;             // [seq][q_head][chunk][2] = (m in log2 units, l)
@@ -448,7 +450,10 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   // Chunk-major launch order: the KV heads of one page are neighbours in memory and run
   // together; every sequence's first chunks run first, and the chunks that only long sequences
   // have (with the empty work-groups of the short ones) come last, which balances ragged batches.
-  const int kvh = blockIdx.x, seq = blockIdx.y, chunk = blockIdx.z;
+  const int kvh = blockIdx.x, chunk = blockIdx.z;
+  // Work-groups start in grid order; a caller-given order lets long sequences start first.
+  const int seq = a.seq_order ? a.seq_order[blockIdx.y] : static_cast<int>(blockIdx.y);
+  if (seq < 0 || seq >= a.n_seqs) return;
   const int L = min(a.seq_lens[seq], a.max_seq_len);
   if (L <= 0) return;
   const int n_pages = (L + kGroup - 1) / kGroup;

@@ -84,22 +84,22 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     bad = pq.Layout(128, 7, 1, 128, 8)
     assert lib.pq_encode_keys(ctypes.byref(bad), null, 0, 1024, 128, 10, null, null, null, 4, null) == -2
     st = lib.pq_decode_attention(ctypes.byref(lay), null, 0, 1, 32, null, null, null, 16, null, 4, null, 1, null, 128,
-                                 0.1, null, null, 0, null, null, 0, null)
+                                 0.1, null, null, 0, null, null, null, 0, null)
     assert st == -1
     fake = ctypes.c_void_p(4096)
     st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 16, null, 4, fake, 1, fake, 128,
-                                0.1, null, 0, null, null, 0, null)
+                                0.1, null, 0, null, null, null, 0, null)
     assert st == -3 and "workspace" in pq.pq_strerror(st)
     # more pages needed than the block table is wide
     st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 16, null, 4, fake, 1, fake, 129,
-                                0.1, null, 0, null, fake, 1 << 20, null)
+                                0.1, null, 0, null, null, fake, 1 << 20, null)
     assert st == -1
     # quantized values need their parameter pool; 3-bit values are not built
     st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 4, null, 4, fake, 1, fake, 128,
-                                0.1, null, 0, null, fake, 1 << 20, null)
+                                0.1, null, 0, null, null, fake, 1 << 20, null)
     assert st == -1
     st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 3, fake, 4, fake, 1, fake, 128,
-                                0.1, null, 0, null, fake, 1 << 20, null)
+                                0.1, null, 0, null, null, fake, 1 << 20, null)
     assert st == -2
     assert pq.pq_vq_bytes_per_page(lay, 4) == 8 * 128 * 64 and pq.pq_vq_bytes_per_page(lay, 2) == 8 * 128 * 32
     assert pq.pq_vq_bytes_per_page(lay, 3) == 0 and pq.pq_vq_params_bytes_per_page(lay) == 8 * 128 * 4
@@ -110,6 +110,7 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     # grouped angles exist for (4,4) and (3,3) only
     grouped = pq.Layout(128, 5, 3, 128, 8, 1)
     st = lib.pq_decode_partials(ctypes.byref(grouped), fake, 0, 1, 32, fake, fake, fake, 16, null, 4, fake, 1, fake, 128,
-                                0.1, null, 0, null, fake, 1 << 20, null)
+                                0.1, null, 0, null, null, fake, 1 << 20, null)
     assert st == -2
-    assert pq.pq_version() >= 101
+    assert lib.pq_order_sequences(null, 5, null, null) == -1 and lib.pq_order_sequences(null, 0, null, null) == 0
+    assert pq.pq_version() >= 102
