@@ -240,7 +240,7 @@ def main() -> int:
                "note": "exactly rounded fp32 radius chain and exact angle classification; not HBM-bound"}
         del keys, e_codes, e_params
 
-    # what this device streams with plain 128-bit loads (context for the roofline fraction)
+    # what this device streams with bare non-temporal 128-bit loads (context for the roofline fraction)
     probe = torch.empty(2 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
     sink = torch.zeros(64, dtype=torch.int32, device="cuda:0")
     for _ in range(3):

@@ -276,10 +276,11 @@ int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_dtype, int3
                   const void* residual_keys, void* hip_stream);
 
 /*
- * pq_probe_read_stream -- measurement aid, not part of the method: a plain
- * 128-bit-load streaming read of `bytes` (multiple of 16) device bytes that
- * XOR-folds them into sink[0..63] (device uint32[64], so the loads cannot be
- * elided).  Timed by the benchmark to report what this device streams from HBM.
+ * pq_probe_read_stream -- measurement aid, not part of the method: a streaming read of
+ * `bytes` (multiple of 16) device bytes with non-temporal 128-bit loads, each wavefront taking
+ * 40 KB blocks as the decode kernel takes pages, XOR-folded into sink[0..63] (device uint32[64],
+ * so the loads cannot be elided).  Timed by the benchmark to report what this device streams
+ * from HBM when no arithmetic is in the way.
  */
 int pq_probe_read_stream(const void* src, size_t bytes, uint32_t* sink, void* hip_stream);
 

@@ -51,20 +51,32 @@ ChunkPlan plan_chunks(int32_t n_seqs, int32_t n_kv_heads, int32_t max_seq_len) {
 
 namespace {
 
-// Each thread XOR-folds a grid-strided sequence of 16-byte words; one word per
-// work-group slot is written so the loads stay live.
-__global__ __launch_bounds__(256) void pq_read_stream_kernel(const uint4* __restrict__ src, size_t n16,
+// What the device streams when nothing else is done: each wavefront reads 40 KB blocks (the size
+// of one page of one KV head: codes + values) with non-temporal 128-bit loads, 8 in flight, and
+// XOR-folds them; one word per work-group slot is written so the loads stay live.
+typedef uint32_t probe_u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void pq_read_stream_kernel(const probe_u32x4* __restrict__ src, size_t n16,
                                                             uint32_t* __restrict__ sink) {
-  const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
-  size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+  constexpr size_t kBlock16 = 2560;                                  // 40 KB in 16-byte words
+  const int lane = threadIdx.x & 63;
+  const size_t wave = (static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x) >> 6;
+  const size_t n_waves = (static_cast<size_t>(gridDim.x) * blockDim.x) >> 6;
+  const size_t n_blocks = n16 / kBlock16;
   uint32_t acc = 0;
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  for (size_t b = wave; b < n_blocks; b += n_waves) {
+    const probe_u32x4* p = src + b * kBlock16 + lane;
+    for (int r0 = 0; r0 < 40; r0 += 8) {
+      probe_u32x4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(p + (r0 + u) * 64);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
   }
-  for (; i < n16; i += stride) {
-    const uint4 a = src[i];
-    acc ^= a.x ^ a.y ^ a.z ^ a.w;
+  // the tail that does not fill a block
+  for (size_t i = n_blocks * kBlock16 + wave * 64 + lane; i < n16; i += n_waves * 64) {
+    const probe_u32x4 v = __builtin_nontemporal_load(src + i);
+    acc ^= v.x ^ v.y ^ v.z ^ v.w;
   }
   if (acc == 0x9e3779b9u) sink[threadIdx.x & 63] = acc;   // practically never true; keeps the loads
 }
@@ -107,8 +119,8 @@ extern "C" size_t pq_values_bytes_per_page(const pq_layout* l) {
 extern "C" int pq_probe_read_stream(const void* src, size_t bytes, uint32_t* sink, void* hip_stream) {
   if (!src || !sink || bytes == 0 || (bytes & 15u) || (reinterpret_cast<uintptr_t>(src) & 15u))
     return PQ_ERR_INVALID_ARG;
-  hipLaunchKernelGGL(pq_read_stream_kernel, dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
-                     static_cast<const uint4*>(src), bytes / 16, sink);
+  hipLaunchKernelGGL(pq_read_stream_kernel, dim3(256 * 8), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<const probe_u32x4*>(src), bytes / 16, sink);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return record_hip_error(e);
   return PQ_OK;
