@@ -404,3 +404,25 @@ def test_sequence_order_hint():
     ident = torch.empty(3000, dtype=torch.int32, device="cuda:0")
     pq_order_sequences(many, ident)
     assert ident.cpu().tolist() == list(range(3000))
+
+
+def test_random_shapes():
+    """Seeded sweep over shapes the fixed cases do not name: random batch sizes, query-group
+    sizes, bit allocations, angle quantizers and ragged lengths (lengths of 0 included)."""
+    rng = np.random.default_rng(20250299)
+    bit_choices = [(4, 4), (3, 3), (5, 3), (3, 5), (4, 2), (2, 4)]
+    for case in range(20):
+        n_kv = int(rng.choice([1, 2, 3, 5]))
+        group = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16]))
+        grouped = bool(rng.random() < 0.4)
+        r, t = (4, 4) if grouped and rng.random() < 0.5 else ((3, 3) if grouped else bit_choices[int(rng.integers(6))])
+        n_seqs = int(rng.integers(1, 7))
+        max_len = int(rng.integers(1, 1400))
+        base = WL["ragged"] if rng.random() < 0.5 else WL["mha"]
+        wl = base.scaled(n_seqs=n_seqs, n_q_heads=n_kv * group, n_kv_heads=n_kv, max_len=max_len, min_len=1,
+                         r_bits=r, t_bits=t, grouped_angles=grouped, index=100 + case,
+                         shuffled_pages=bool(rng.random() < 0.5),
+                         key_dtype="f32" if rng.random() < 0.3 else "f16")
+        lens = rng.integers(0, max_len + 1, n_seqs).astype(np.int32)
+        lens[int(rng.integers(n_seqs))] = max_len
+        _check_workload(f"random_{case}", wl, lens)
