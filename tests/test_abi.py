@@ -114,3 +114,11 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert st == -2
     assert lib.pq_order_sequences(null, 5, null, null) == -1 and lib.pq_order_sequences(null, 0, null, null) == 0
     assert pq.pq_version() >= 102
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is single-GPU by construction: --gpus 2 exits with a message before touching the device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
