@@ -1,6 +1,13 @@
 // Host entry points of the decode path (pq_decode_*, pq_score_keys) and the chunk merge kernel.
 // The attention and score-only kernel templates live in pq_decode_kernels.hpp.
 #include "pq_decode_kernels.hpp"
+#include "pq_decode_roles.hpp"
+
+// Which attention kernel serves fp16 values with the uniform angle grid: the role-specialised
+// one (1) or the one whose wavefronts alternate between a score and a value phase (0).
+#ifndef PQ_USE_ROLES
+#define PQ_USE_ROLES 1
+#endif
 
 namespace pq {
 
@@ -255,6 +262,9 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
     } else if (v_bits != 16) {
       e = launch_partials_vq(rt, G, v_bits, a, q_dtype, grid, stream);
       if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;   // quantized values: (r,t) = (4,4), (3,3) only
+    } else if (PQ_USE_ROLES) {
+      e = launch_partials_roles(rt, G, a, q_dtype, grid, stream);
+      if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;
     } else {
       switch (rt) {
         case 44: e = launch_partials_g<4, 4>(G, a, q_dtype, grid, stream); break;

@@ -1,0 +1,46 @@
+// Instantiations of the role-specialised attention kernel (fp16 values, uniform angle grid).
+#include "pq_decode_roles.hpp"
+
+namespace pq {
+namespace {
+
+template <int G, int RB, int TB>
+void launch_one(const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st) {
+  const bool sc = a.scores != nullptr;
+  if (qdt == PQ_F16) {
+    if (sc) hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, __half, true>), grid, dim3(kThreads), 0, st, a);
+    else    hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, __half, false>), grid, dim3(kThreads), 0, st, a);
+  } else {
+    if (sc) hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, float, true>), grid, dim3(kThreads), 0, st, a);
+    else    hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, float, false>), grid, dim3(kThreads), 0, st, a);
+  }
+}
+
+template <int RB, int TB>
+bool launch_g(int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st) {
+  switch (G) {
+    case 1: launch_one<1, RB, TB>(a, qdt, grid, st); return true;
+    case 2: launch_one<2, RB, TB>(a, qdt, grid, st); return true;
+    case 4: launch_one<4, RB, TB>(a, qdt, grid, st); return true;
+    default: return false;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_partials_roles(int rt, int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st) {
+  bool ok = false;
+  switch (rt) {
+    case 44: ok = launch_g<4, 4>(G, a, qdt, grid, st); break;
+    case 33: ok = launch_g<3, 3>(G, a, qdt, grid, st); break;
+    case 53: ok = launch_g<5, 3>(G, a, qdt, grid, st); break;
+    case 35: ok = launch_g<3, 5>(G, a, qdt, grid, st); break;
+    case 42: ok = launch_g<4, 2>(G, a, qdt, grid, st); break;
+    case 24: ok = launch_g<2, 4>(G, a, qdt, grid, st); break;
+    default: break;
+  }
+  if (!ok) return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+}  // namespace pq
