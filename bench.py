@@ -7,7 +7,7 @@ merge -- over one batch of synthetic sequences (one decode step per sequence).
 The cache is encoded beforehand by pq_encode_keys and is resident in HBM when
 the timed region starts.  The metric is keys scored per second (query-head x
 cached-token scores); the roofline object prices the dominant kernel
-(pq_decode_partials) against the 8 TB/s HBM peak using the algorithmic bytes of
+(the attention kernel behind pq_decode_partials) against the 8 TB/s HBM peak using the algorithmic bytes of
 the packed cache: per (KV head, token) 64*w/8 B of codes + 2 B of radius
 parameters + 256 B of fp16 values.
 
@@ -267,7 +267,9 @@ def main() -> int:
                    "cache_copies_rotated": n_copies, "longest_first_order": cache.seq_order is not None,
                    "keys_scored_per_step": keys_scored,
                    "kv_tokens_per_step": int(lens.astype(np.int64).sum()) * wl.n_kv_heads},
-        "roofline": {"bound": "hbm", "kernel": "pq_decode_partials_kernel", "achieved": achieved,
+        "roofline": {"bound": "hbm",
+                     "kernel": "pq_decode_roles_kernel" if (args.v_bits == 16 and not wl.grouped_angles)
+                     else "pq_decode_partials_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": read_traffic_note(wl.name) if args.v_bits == 16 and not wl.grouped_angles else None,
                      "algorithmic_bytes": alg_bytes,

@@ -8,11 +8,11 @@ template <int G, int RB, int TB>
 void launch_one(const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st) {
   const bool sc = a.scores != nullptr;
   if (qdt == PQ_F16) {
-    if (sc) hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, __half, true>), grid, dim3(kThreads), 0, st, a);
-    else    hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, __half, false>), grid, dim3(kThreads), 0, st, a);
+    if (sc) hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, __half, true>), grid, dim3(kRoleThreads), 0, st, a);
+    else    hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, __half, false>), grid, dim3(kRoleThreads), 0, st, a);
   } else {
-    if (sc) hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, float, true>), grid, dim3(kThreads), 0, st, a);
-    else    hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, float, false>), grid, dim3(kThreads), 0, st, a);
+    if (sc) hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, float, true>), grid, dim3(kRoleThreads), 0, st, a);
+    else    hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, float, false>), grid, dim3(kRoleThreads), 0, st, a);
   }
 }
 

@@ -25,10 +25,14 @@ hipError_t launch_partials_roles(int rt, int G, const DecodeArgs& a, pq_dtype qd
 
 namespace {
 
-constexpr int kPairsOfWaves = 2;
+#ifndef PQ_ROLES_NP
+#define PQ_ROLES_NP 2
+#endif
+constexpr int kPairsOfWaves = PQ_ROLES_NP;         // (score, value) wavefront pairs per work-group
+constexpr int kRoleThreads = kPairsOfWaves * 128;
 
 template <int G, int RB, int TB, typename QT, bool SCORES>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
+__global__ __launch_bounds__(kRoleThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void pq_decode_roles_kernel(const DecodeArgs a) {
   constexpr int W = RB + TB;
   constexpr int UB = 2 * W;
@@ -57,18 +61,18 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int pair = wave & 1;               // which half of the chunk's pages
-  const bool scorer = wave < 2;            // role of this wavefront
+  const int pair = wave % kPairsOfWaves;   // which share of the chunk's pages
+  const bool scorer = wave < kPairsOfWaves;   // role of this wavefront
   const int row = lane >> 4, col = lane & 15;
   const int my_head = (G == 4) ? row : (G == 2 ? (row >> 1) : 0);
   const bool owner = (G == 4) || (G == 2 && (row & 1) == 0) || (G == 1 && row == 0);
 
   // pages of this pair: chunk pages pair, pair + 2, ...; the step count is the same for both pairs
-  const int n_p = npg > pair ? (npg - pair + 1) / 2 : 0;
-  const int n_steps = (npg + 1) / 2 + 1;   // pair 0's page count, plus one step of skew between the roles
+  const int n_p = npg > pair ? (npg - pair + kPairsOfWaves - 1) / kPairsOfWaves : 0;
+  const int n_steps = (npg + kPairsOfWaves - 1) / kPairsOfWaves + 1;   // pair 0's page count, plus one step of skew
   int pid_lane = -1;
   if (lane < n_p) {
-    const int64_t pid = a.block_table[static_cast<int64_t>(seq) * a.max_pages_per_seq + page0 + pair + 2 * lane];
+    const int64_t pid = a.block_table[static_cast<int64_t>(seq) * a.max_pages_per_seq + page0 + pair + kPairsOfWaves * lane];
     if (pid >= 0 && pid < a.n_pool_pages) pid_lane = static_cast<int>(pid);
   }
   constexpr uint32_t kCodesBytes = kBlocks * kGroup * UB;
@@ -79,7 +83,7 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
   {
     const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim;
     float* lf = reinterpret_cast<float*>(lut);
-    for (int idx = tid; idx < kPairs * NA; idx += kThreads) {
+    for (int idx = tid; idx < kPairs * NA; idx += kRoleThreads) {
       const int j = idx >> TB, s = idx & (NA - 1);
       const float cs = a.cos_tab[s], sn = a.sin_tab[s];
 #pragma unroll
@@ -107,14 +111,14 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
       const int pid = __builtin_amdgcn_readlane(pid_lane, k & 63);
       const bool ok = pid >= 0 && k < n_p;
       const int64_t ph = ok ? static_cast<int64_t>(pid) * a.n_kv_heads + kvh : 0;
-      nv = ok ? min(kGroup, L - (page0 + pair + 2 * k) * kGroup) : 0;
-      const bool packed = ok && (page0 + pair + 2 * k) != res_page;
+      nv = ok ? min(kGroup, L - (page0 + pair + kPairsOfWaves * k) * kGroup) : 0;
+      const bool packed = ok && (page0 + pair + kPairsOfWaves * k) != res_page;
       rc = make_rsrc(a.codes + ph * kCodesBytes, packed ? kCodesBytes : 0u);
       rp = make_rsrc(a.params + ph * kPairs, packed ? kPairs * 4u : 0u);
     };
 
     // residual group (plain dot products), if this pair owns its page
-    if (res_page >= page0 + pair && res_page < page0 + npg && ((res_page - page0 - pair) & 1) == 0) {
+    if (res_page >= page0 + pair && res_page < page0 + npg && ((res_page - page0 - pair) % kPairsOfWaves) == 0) {
       const int nv_res = L - res_page * kGroup;
       const __amdgpu_buffer_rsrc_t rs_res = make_rsrc(
           a.residual + (static_cast<int64_t>(seq) * a.n_kv_heads + kvh) * (kGroup * kHeadDim),
@@ -151,7 +155,7 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
 
     for (int t = 0; t < n_steps; ++t) {
       if (t < n_p) {
-        const int pi = page0 + pair + 2 * t;
+        const int pi = page0 + pair + kPairsOfWaves * t;
         page_setup(t + 1, rc_nxt, rp_nxt, nv_nxt);
         float sf[16], zz[16];
 #pragma unroll
@@ -232,7 +236,7 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
       const int pid = __builtin_amdgcn_readlane(pid_lane, k & 63);
       const bool ok = pid >= 0 && k < n_p;
       const int64_t ph = ok ? static_cast<int64_t>(pid) * a.n_kv_heads + kvh : 0;
-      const int nv = ok ? min(kGroup, L - (page0 + pair + 2 * k) * kGroup) : 0;
+      const int nv = ok ? min(kGroup, L - (page0 + pair + kPairsOfWaves * k) * kGroup) : 0;
       rot = ok ? (pid * 13 + kvh * 5) & 31 : 0;
       rv = make_rsrc(a.values + ph * (kGroup * kHeadDim), static_cast<uint32_t>(nv) * (kHeadDim * 2));
     };
@@ -294,9 +298,11 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
   __syncthreads();
 
   // ---- fold the two pairs into one partial per query head ----
-  for (int idx = tid; idx < G * kHeadDim; idx += kThreads) {
+  for (int idx = tid; idx < G * kHeadDim; idx += kRoleThreads) {
     const int h = idx >> 7, dim = idx & (kHeadDim - 1);
-    const float M = fmaxf(red_ml[0][h][0], red_ml[1][h][0]);
+    float M = red_ml[0][h][0];
+#pragma unroll
+    for (int w = 1; w < kPairsOfWaves; ++w) M = fmaxf(M, red_ml[w][h][0]);
     float o = 0.f, l = 0.f;
     if (M > kNegInf) {
 #pragma unroll
