@@ -262,7 +262,9 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
     } else if (v_bits != 16) {
       e = launch_partials_vq(rt, G, v_bits, a, q_dtype, grid, stream);
       if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;   // quantized values: (r,t) = (4,4), (3,3) only
-    } else if (PQ_USE_ROLES) {
+    } else if (PQ_USE_ROLES && static_cast<int64_t>(grid.x) * grid.y * grid.z >= 256) {
+      // launches of a few work-groups stay with the kernel whose four wavefronts share a chunk's
+      // pages four ways (measured: 9 against 12 us for one head over 4096 tokens)
       e = launch_partials_roles(rt, G, a, q_dtype, grid, stream);
       if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;
     } else {
