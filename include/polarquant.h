@@ -234,6 +234,15 @@ int pq_decode_merge(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
                     const void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * pq_decode_kernel_name -- name of the attention kernel pq_decode_partials / pq_decode_attention
+ * launch for this shape ("" on invalid arguments).  The choice depends on the launch shape (see
+ * pq_decode_partials); profiles and the benchmark use this to name the kernel that really ran.
+ * The string is static storage.
+ */
+const char* pq_decode_kernel_name(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
+                                  int32_t max_seq_len, int32_t v_bits);
+
+/*
  * pq_order_sequences -- writes into order_out (device int32 [n_seqs]) the sequence indices sorted
  * by decreasing seq_lens (ties by index), for the seq_order argument of the decode calls.  One small
  * kernel; batches of more than 2048 sequences get the identity order.

@@ -168,6 +168,17 @@ void fill_angle_tables(DecodeArgs& a, int t_bits) {
   }
 }
 
+// Which attention kernel a launch gets.  The role-specialised kernel serves fp16 values with the
+// uniform angle grid when the launch has at least 256 work-groups; launches of a few work-groups
+// stay with the kernel whose four wavefronts share a chunk's pages four ways (measured: 9
+// against 12 us for one head over 4096 tokens).
+enum class AttentionKernel { kPartials, kRoles };
+AttentionKernel choose_attention_kernel(const pq_layout* l, int32_t v_bits, int64_t n_groups) {
+  if (PQ_USE_ROLES && l->angle_quantizer == PQ_ANGLE_UNIFORM && v_bits == 16 && n_groups >= 256)
+    return AttentionKernel::kRoles;
+  return AttentionKernel::kPartials;
+}
+
 int check_decode_shape(const pq_layout* l, int32_t n_seqs, int32_t n_q_heads, int32_t max_seq_len) {
   if (!l || n_seqs <= 0 || n_q_heads <= 0 || max_seq_len <= 0) return PQ_ERR_INVALID_ARG;
   if (l->n_kv_heads <= 0 || n_q_heads % l->n_kv_heads != 0) return PQ_ERR_INVALID_ARG;
@@ -262,9 +273,8 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
     } else if (v_bits != 16) {
       e = launch_partials_vq(rt, G, v_bits, a, q_dtype, grid, stream);
       if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;   // quantized values: (r,t) = (4,4), (3,3) only
-    } else if (PQ_USE_ROLES && static_cast<int64_t>(grid.x) * grid.y * grid.z >= 256) {
-      // launches of a few work-groups stay with the kernel whose four wavefronts share a chunk's
-      // pages four ways (measured: 9 against 12 us for one head over 4096 tokens)
+    } else if (choose_attention_kernel(layout, v_bits, static_cast<int64_t>(grid.x) * grid.y * grid.z) ==
+               AttentionKernel::kRoles) {
       e = launch_partials_roles(rt, G, a, q_dtype, grid, stream);
       if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;
     } else {
@@ -282,6 +292,15 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
   }
   if (e != hipSuccess) return record_hip_error(e);
   return PQ_OK;
+}
+
+extern "C" const char* pq_decode_kernel_name(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
+                                             int32_t max_seq_len, int32_t v_bits) {
+  if (check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len) != PQ_OK) return "";
+  const ChunkPlan plan = plan_chunks(n_seqs, layout->n_kv_heads, max_seq_len);
+  const int64_t n_groups = static_cast<int64_t>(layout->n_kv_heads) * n_seqs * plan.n_chunks;
+  return choose_attention_kernel(layout, v_bits, n_groups) == AttentionKernel::kRoles
+             ? "pq_decode_roles_kernel" : "pq_decode_partials_kernel";
 }
 
 extern "C" int pq_order_sequences(const int32_t* seq_lens, int32_t n_seqs, int32_t* order_out, void* hip_stream) {

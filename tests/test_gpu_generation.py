@@ -23,20 +23,46 @@ def _say(msg):
 
 @pytest.mark.parametrize("bits", [(4, 4, False), (3, 3, False), (4, 4, True), (3, 3, True)])
 def test_append_then_decode_with_residual(bits):
-    import paper_2502_00527_amd as pq
-    from paper_2502_00527_amd.cache import make_layout
-
     r, t, grouped = bits
     wl = W.WORKLOADS["gqa"].scaled(n_seqs=3, n_q_heads=8, n_kv_heads=2, max_len=1024, min_len=1024,
                                    r_bits=r, t_bits=t, shuffled_pages=True, grouped_angles=grouped)
+    _generate(wl, np.array([300, 128, 5], np.int32), 260, (1, 84, 123, 124, 200, 260))
+
+
+@pytest.mark.parametrize("bits", [(4, 4, 4, "f16"), (3, 3, 2, "f16"), (5, 3, 1, "f16"), (2, 4, 4, "f32"),
+                                  (3, 5, 6, "f16"), (4, 2, 2, "f32")])
+def test_append_then_decode_large_batch(bits):
+    """The same run with 256 (sequence, KV head) units, which the role-specialised attention kernel
+    serves: residual groups of every fill level at once (the start lengths differ by 5 tokens from
+    sequence to sequence), on first, middle and last pages of a chunk and on either wavefront pair."""
+    from paper_2502_00527_amd import pq_decode_kernel_name
+    from paper_2502_00527_amd.cache import make_layout
+
+    r, t, group, dt = bits
+    S, H = 64, 4
+    wl = W.WORKLOADS["gqa"].scaled(n_seqs=S, n_q_heads=H * group, n_kv_heads=H, max_len=1024, min_len=1024,
+                                   r_bits=r, t_bits=t, shuffled_pages=True, key_dtype=dt)
+    start = (300 + 5 * np.arange(S)).astype(np.int32)          # 300 .. 615: residual groups on pages 2 .. 5
+    start[10], start[11], start[12], start[20], start[21] = 128, 256, 127, 3, 0
+    steps = 131
+    assert pq_decode_kernel_name(make_layout(wl), S, wl.n_q_heads, int(start.max()) + steps) == "pq_decode_roles_kernel"
+    _generate(wl, start, steps, (1, 64, 131), sample=list(range(0, S, 3)) + [10, 11, 12])
+
+
+def _generate(wl, start, steps, check_at, sample=None):
+    import paper_2502_00527_amd as pq
+    from paper_2502_00527_amd.cache import make_layout
+
+    r, t, grouped = wl.r_bits, wl.t_bits, wl.grouped_angles
     layout = make_layout(wl)
     g, H, d, S = wl.group_tokens, wl.n_kv_heads, wl.head_dim, wl.n_seqs
-    start = np.array([300, 128, 5], np.int32)
-    steps = 260
+    sample = list(range(S)) if sample is None else sorted(set(sample))
     final = start + steps
     table, total = W.page_table(wl, final)
     dev = "cuda:0"
-    keys_all = [W.keys_for_seq(wl, s, int(final[s])) for s in range(S)]          # fp16 [L, H, d]
+    # keys are fp16 values (the residual buffer keeps fp16 rows); with an fp32 workload they are
+    # handed over as fp32 numbers that fp16 represents exactly, the queries stay genuine fp32
+    keys_all = [W.keys_for_seq(wl, s, int(final[s])).astype(np.float16).astype(wl.np_key_dtype) for s in range(S)]
     vals_all = [W.values_for_seq(wl, s, int(final[s])) for s in range(S)]
     q_h = W.queries(wl)
     ub = 2 * (r + t)
@@ -77,8 +103,11 @@ def test_append_then_decode_with_residual(bits):
             assert torch.equal(qk[s, :, : int(cur[s])], scores[s, :, : int(cur[s])])
             assert torch.isnan(qk[s, :, int(cur[s]):]).all()
         worst_s = worst_o = 0.0
-        for s in range(S):
+        for s in sample:
             L = int(cur[s])
+            if L == 0:
+                assert not out[s].cpu().numpy().any(), "empty sequence must give a zero output row"
+                continue
             n_full = L // g
             parts = []
             if n_full:
@@ -92,7 +121,7 @@ def test_append_then_decode_with_residual(bits):
             err = score_errors(scores[s, :, :L].cpu().numpy(), ref_scores, q_h[s], k_ref)
             worst_s = max(worst_s, float(err.max()))
             worst_o = max(worst_o, float(np.abs(out[s].cpu().numpy() - ref_out).max()))
-        _say(f"[generation r{r}t{t}{' grouped angles' if grouped else ''}] step {step_no}: lens {cur.tolist()} score err {worst_s:.2e} out err {worst_o:.2e}")
+        _say(f"[generation r{r}t{t}{' grouped angles' if grouped else ''}] step {step_no}: lens {cur.tolist()[:8]}{'...' if S > 8 else ''} score err {worst_s:.2e} out err {worst_o:.2e}")
         assert worst_s <= SCORE_REL and worst_o <= OUT_ABS
 
     check(0)
@@ -100,12 +129,14 @@ def test_append_then_decode_with_residual(bits):
         new = np.stack([keys_all[s][int(start[s]) + i] for s in range(S)])           # [S, H, d]
         pq.pq_append_keys(layout, torch.from_numpy(new).to(dev), residual, lens, bt, codes, params)
         lens += 1
-        if i + 1 in (1, 84, 123, 124, 200, 260):
+        if i + 1 in check_at:
             check(i + 1)
 
     # every group completed on the way is encoded bit-exactly as the oracle encodes it
-    for s in range(S):
+    for s in sample:
         n_full = int(final[s]) // g
+        if n_full == 0:
+            continue
         enc = polar.encode_keys(keys_all[s][: n_full * g], r, t, g, grouped_angles=grouped)
         want_codes, want_params = cache_format.pack_sequence(enc["a"], enc["c"], enc["scale"], enc["zero"], r, t, g,
                                                              enc.get("t_scale"), enc.get("t_zero"))

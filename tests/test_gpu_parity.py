@@ -57,8 +57,54 @@ SMALL = {
 }
 
 
-def _check_workload(name, wl, lens, sample_seqs=None, check_scores=True):
-    from paper_2502_00527_amd.cache import build_device_cache
+# Launches of at least 256 work-groups with fp16 values and the uniform grid are served by the
+# role-specialised attention kernel; these cases stay small for the oracle (a few hundred tokens
+# per sequence) but have enough (sequence, KV head, chunk) units to be dispatched to it.  Between
+# them they cover every bit allocation, both query dtypes, query groups of 1, 2, 4 and the
+# multi-pass groups 6 and 8, chunks with an odd page count, ragged and empty sequences.
+_BIG = dict(n_seqs=32, n_kv_heads=8, max_len=777, min_len=777)
+LARGE_GRID = {
+    "big_r4t4_g4": (WL["gqa"].scaled(n_q_heads=32, **_BIG), None),
+    "big_r3t3_g4": (WL["gqa"].scaled(n_q_heads=32, r_bits=3, t_bits=3, **_BIG), None),
+    "big_r5t3_g4": (WL["gqa"].scaled(n_q_heads=32, r_bits=5, t_bits=3, **_BIG), None),
+    "big_r3t5_g2": (WL["gqa"].scaled(n_q_heads=16, r_bits=3, t_bits=5, **_BIG), None),
+    "big_r4t2_g1": (WL["gqa"].scaled(n_q_heads=8, r_bits=4, t_bits=2, **_BIG), None),
+    "big_r2t4_g4": (WL["gqa"].scaled(n_q_heads=32, r_bits=2, t_bits=4, **_BIG), None),
+    "big_r5t3_g1": (WL["mha"].scaled(n_q_heads=8, r_bits=5, t_bits=3, **_BIG), None),
+    "big_r2t4_g2": (WL["mha"].scaled(n_q_heads=16, r_bits=2, t_bits=4, **_BIG), None),
+    "big_fp32_r4t4_g4": (WL["gqa"].scaled(n_q_heads=32, key_dtype="f32", **_BIG), None),
+    "big_fp32_r3t3_g2": (WL["gqa"].scaled(n_q_heads=16, key_dtype="f32", r_bits=3, t_bits=3, **_BIG), None),
+    "big_fp32_r3t5_g1": (WL["gqa"].scaled(n_q_heads=8, key_dtype="f32", r_bits=3, t_bits=5, **_BIG), None),
+    "big_group_of_six": (WL["gqa"].scaled(n_q_heads=48, **_BIG), None),                           # 4 + 2
+    "big_group_of_eight_r3t3": (WL["gqa"].scaled(n_q_heads=64, r_bits=3, t_bits=3, **_BIG), None),  # 4 + 4
+    "big_group_of_seven_r4t2": (WL["gqa"].scaled(n_q_heads=56, r_bits=4, t_bits=2, **_BIG), None),  # 4 + 2 + 1
+    "big_ragged_with_empty": (WL["ragged"].scaled(n_seqs=48, n_q_heads=32, n_kv_heads=8, max_len=1500, min_len=1),
+                              "ragged_with_zeros"),
+    "big_ragged_r3t3": (WL["ragged"].scaled(n_seqs=40, n_q_heads=16, n_kv_heads=8, max_len=2100, min_len=1,
+                                            r_bits=3, t_bits=3), "ragged_with_zeros"),
+}
+
+
+def _lengths(wl, spec):
+    if isinstance(spec, str) and spec == "ragged_with_zeros":
+        lens = W.seq_lengths(wl).copy()
+        lens[3] = 0
+        lens[wl.n_seqs - 1] = 0
+        lens[5] = wl.max_len
+        lens[7] = 128
+        lens[8] = 129
+        lens[9] = 1
+        return lens
+    return spec
+
+
+def _check_workload(name, wl, lens, sample_seqs=None, check_scores=True, expect_kernel=None):
+    from paper_2502_00527_amd import pq_decode_kernel_name
+    from paper_2502_00527_amd.cache import build_device_cache, make_layout
+
+    if expect_kernel is not None:
+        max_len = wl.max_len if lens is None else int(max(1, np.max(lens)))
+        assert pq_decode_kernel_name(make_layout(wl), wl.n_seqs, wl.n_q_heads, max_len) == expect_kernel
 
     _say(f"[parity] {name}: S={wl.n_seqs} Hq={wl.n_q_heads} Hkv={wl.n_kv_heads} L<={wl.max_len} "
          f"r{wl.r_bits}t{wl.t_bits} {wl.key_dtype}")
@@ -107,6 +153,13 @@ def _check_workload(name, wl, lens, sample_seqs=None, check_scores=True):
 def test_small_case(name):
     wl, lens = SMALL[name]
     _check_workload(name, wl, lens)
+
+
+@pytest.mark.parametrize("name", list(LARGE_GRID))
+def test_large_grid_case(name):
+    """Small sequences, many of them: the launch shape that selects the role-specialised kernel."""
+    wl, spec = LARGE_GRID[name]
+    _check_workload(name, wl, _lengths(wl, spec), expect_kernel="pq_decode_roles_kernel")
 
 
 def test_decode_on_oracle_packed_bytes():
@@ -269,6 +322,45 @@ def test_block_table_entry_outside_pool_is_masked():
         assert np.abs(out[s] - want).max() <= OUT_ABS
 
 
+def test_masked_pages_in_a_large_grid():
+    """Block-table entries outside the pool (too large, negative) in a launch served by the
+    role-specialised kernel: those pages count as masked, for either wavefront pair of a
+    work-group and for first, middle and last pages of a chunk."""
+    from oracle import attention
+    from paper_2502_00527_amd import pq_decode_kernel_name
+    from paper_2502_00527_amd.cache import build_device_cache
+
+    wl = WL["gqa"].scaled(n_seqs=32, n_q_heads=32, n_kv_heads=8, max_len=1100, min_len=1100)
+    cache = build_device_cache(wl)
+    assert pq_decode_kernel_name(cache.layout, wl.n_seqs, wl.n_q_heads, cache.max_seq_len) == "pq_decode_roles_kernel"
+    # sequence 20 loses the whole of its first chunk (8 pages), sequence 21 every page
+    masked = {0: [0], 1: [3], 2: [1, 2], 5: [8], 9: [4, 7], 17: [0, 1, 2, 3], 20: list(range(8)),
+              21: list(range(9)), 31: [5]}
+    bt = cache.block_table.clone()
+    for k, (s, pages) in enumerate(masked.items()):
+        for p in pages:
+            bt[s, p] = (cache.n_pool_pages + 7 + p) if (k + p) % 2 == 0 else -1 - p
+    cache.block_table = bt
+    _say("[parity] masked_pages_large_grid: decode launch")
+    out = cache.decode().cpu().numpy()
+    torch.cuda.synchronize()
+    q_h = W.queries(wl)
+    g = wl.group_tokens
+    worst = 0.0
+    assert not out[21].any(), "a sequence whose pages are all masked must give a zero output row"
+    for s in sorted((set(masked) - {21}) | {3, 30}):
+        ref = OracleSeq(wl, s, 1100)
+        _, _, k_hat = ref.attend(q_h[s], cache.sm_scale)
+        keep = np.ones(1100, bool)
+        for p in masked.get(s, []):
+            keep[p * g:(p + 1) * g] = False
+        v = W.values_for_seq(wl, s, 1100).astype(np.float64)
+        _, want = attention.attend(q_h[s].astype(np.float64), k_hat[keep], v[keep], cache.sm_scale)
+        worst = max(worst, float(np.abs(out[s] - want).max()))
+    _say(f"[parity] masked_pages_large_grid: max_out_err={worst:.3e}")
+    assert worst <= OUT_ABS
+
+
 # ---- full-size launch configurations (what the benchmark times), sampled sequences ----
 
 FULL = {
@@ -426,3 +518,29 @@ def test_random_shapes():
         lens = rng.integers(0, max_len + 1, n_seqs).astype(np.int32)
         lens[int(rng.integers(n_seqs))] = max_len
         _check_workload(f"random_{case}", wl, lens)
+
+
+def test_random_shapes_many_units():
+    """The same kind of sweep with enough (sequence, KV head) units that the launches cross the
+    256-work-group line: fp16 values with the uniform grid then run the role-specialised kernel."""
+    from paper_2502_00527_amd import pq_decode_kernel_name
+    from paper_2502_00527_amd.cache import make_layout
+
+    rng = np.random.default_rng(20250298)
+    bit_choices = [(4, 4), (3, 3), (5, 3), (3, 5), (4, 2), (2, 4)]
+    n_roles = 0
+    for case in range(10):
+        n_kv = int(rng.choice([4, 8, 6]))
+        group = int(rng.choice([1, 2, 3, 4, 5, 8]))
+        r, t = bit_choices[int(rng.integers(6))]
+        n_seqs = int(rng.integers(256 // n_kv, 400 // n_kv))
+        max_len = int(rng.integers(300, 900))
+        base = WL["ragged"] if rng.random() < 0.5 else WL["mha"]
+        wl = base.scaled(n_seqs=n_seqs, n_q_heads=n_kv * group, n_kv_heads=n_kv, max_len=max_len, min_len=1,
+                         r_bits=r, t_bits=t, index=200 + case, shuffled_pages=bool(rng.random() < 0.5),
+                         key_dtype="f32" if rng.random() < 0.3 else "f16")
+        lens = rng.integers(0, max_len + 1, n_seqs).astype(np.int32)
+        lens[int(rng.integers(n_seqs))] = max_len
+        n_roles += pq_decode_kernel_name(make_layout(wl), n_seqs, wl.n_q_heads, max_len) == "pq_decode_roles_kernel"
+        _check_workload(f"random_many_{case}", wl, lens, sample_seqs=list(range(0, n_seqs, 3)))
+    assert n_roles >= 8
