@@ -80,7 +80,9 @@ typedef enum {
   PQ_ERR_INVALID_ARG = -1,   /* null pointer, negative size, inconsistent shapes */
   PQ_ERR_UNSUPPORTED = -2,   /* a layout this build has no kernel for */
   PQ_ERR_WORKSPACE = -3,     /* workspace missing, misaligned or too small */
-  PQ_ERR_HIP = -4            /* a HIP call failed; see pq_last_hip_error() */
+  PQ_ERR_HIP = -4,           /* a HIP call failed; see pq_last_hip_error() */
+  PQ_ERR_STATIC_LIMIT = -5   /* pq_decode_attention_static: the shape needs more scratch than
+                                PQ_STATIC_SCRATCH_BYTES */
 } pq_status;
 
 typedef enum { PQ_F16 = 0, PQ_F32 = 1 } pq_dtype;
@@ -211,6 +213,33 @@ int pq_decode_attention(const pq_layout* layout, const void* q, pq_dtype q_dtype
                         float sm_scale, float* out, float* scores, int64_t scores_stride,
                         const void* residual_keys, const int32_t* seq_order, void* workspace,
                         size_t workspace_bytes, void* hip_stream);
+
+/*
+ * pq_decode_attention_static -- pq_decode_attention for callers that cannot allocate device
+ * memory and have no workspace to hand over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, kernels and results as pq_decode_attention,
+ * without `workspace` / `workspace_bytes`: the chunk partials go to a static device array of
+ * PQ_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until the process ends).
+ * The call allocates and frees nothing.
+ *   - A shape whose pq_decode_workspace_bytes(...) exceeds PQ_STATIC_SCRATCH_BYTES is rejected with
+ *     PQ_ERR_STATIC_LIMIT before anything is launched.  8 MiB covers e.g. 16 sequences x 32 query
+ *     heads x 32K tokens (2.1 MiB), 64 ragged sequences of up to 16K tokens (4.2 MiB), one
+ *     sequence of 4M tokens.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on the same GPU
+ *     (two streams, two host threads) race on it and give wrong results.  Calls ordered on one
+ *     stream are safe; the array's contents after a call are scratch and nothing in it needs to be
+ *     cleared between calls (every slot a call reads it has written before).
+ *   - The array's device address is looked up (hipGetSymbolAddress) on the first call on each
+ *     device, with that device current; make that first call outside a graph capture.
+ */
+#define PQ_STATIC_SCRATCH_BYTES (8u << 20)
+int pq_decode_attention_static(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
+                               int32_t n_q_heads, const void* codes_pool, const void* params_pool,
+                               const void* v_pool, int32_t v_bits, const void* v_params_pool,
+                               int64_t n_pool_pages, const int32_t* block_table,
+                               int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
+                               float sm_scale, float* out, float* scores, int64_t scores_stride,
+                               const void* residual_keys, const int32_t* seq_order, void* hip_stream);
 
 /*
  * The two stages of pq_decode_attention, callable on their own (the benchmark

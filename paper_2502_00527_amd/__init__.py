@@ -24,9 +24,11 @@ __all__ = [
     "pq_decode_attention", "pq_decode_partials", "pq_decode_merge", "pq_score_keys", "pq_append_keys",
     "pq_vq_bytes_per_page", "pq_vq_params_bytes_per_page", "pq_encode_values",
     "pq_probe_read_stream", "pq_order_sequences", "pq_decode_kernel_name",
+    "pq_decode_attention_static", "PQ_STATIC_SCRATCH_BYTES",
 ]
 
 PQ_F16, PQ_F32 = 0, 1
+PQ_STATIC_SCRATCH_BYTES = 8 << 20
 _LIB_NAME = "libpolarquant.so"
 _lib = None
 
@@ -62,6 +64,9 @@ _SIGNATURES = {
     "pq_decode_attention": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                     c_int32, c_void_p, c_int64, c_void_p, c_int32, c_void_p, c_int32, c_float, c_void_p,
                                     c_void_p, c_int64, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "pq_decode_attention_static": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
+                                           c_int32, c_void_p, c_int64, c_void_p, c_int32, c_void_p, c_int32, c_float,
+                                           c_void_p, c_void_p, c_int64, c_void_p, c_void_p, c_void_p]),
     "pq_decode_partials": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                    c_int32, c_void_p, c_int64, c_void_p, c_int32, c_void_p, c_int32, c_float, c_void_p,
                                    c_int64, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
@@ -242,6 +247,23 @@ def pq_decode_attention(layout: Layout, q, codes_pool, params_pool, v_pool, bloc
         _order_ptr(seq_order, c["n_seqs"]),
         _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream())
     _check(st, "pq_decode_attention")
+
+
+def pq_decode_attention_static(layout: Layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens,
+                               max_seq_len: int, sm_scale: float, out, scores=None, residual=None,
+                               v_bits: int = 16, v_params=None, seq_order=None) -> None:
+    """pq_decode_attention without a workspace argument (the library's static scratch array)."""
+    import torch
+    c = _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens, v_bits, v_params)
+    st = load_library().pq_decode_attention_static(
+        ctypes.byref(layout), c["q"], c["qk"], c["n_seqs"], c["n_q"], c["codes"], c["params"], c["v"],
+        c["vbits"], c["vpar"], c["n_pool"], c["bt"], c["width"], c["lens"], max_seq_len, sm_scale,
+        _dev_ptr(out, "out", (torch.float32,)),
+        None if scores is None else _dev_ptr(scores, "scores", (torch.float32,)),
+        0 if scores is None else scores.shape[-1],
+        None if residual is None else _dev_ptr(residual, "residual", (torch.float16,)),
+        _order_ptr(seq_order, c["n_seqs"]), _stream())
+    _check(st, "pq_decode_attention_static")
 
 
 def pq_decode_partials(layout: Layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens,

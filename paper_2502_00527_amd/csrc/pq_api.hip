@@ -95,6 +95,7 @@ extern "C" const char* pq_strerror(int status) {
     case PQ_ERR_UNSUPPORTED: return "layout or shape not supported by this build";
     case PQ_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case PQ_ERR_HIP: return "a HIP call failed (see pq_last_hip_error)";
+    case PQ_ERR_STATIC_LIMIT: return "shape needs more scratch than the static buffer of pq_decode_attention_static holds";
     default: return "unknown status";
   }
 }

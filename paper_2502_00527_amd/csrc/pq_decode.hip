@@ -1,5 +1,7 @@
 // Host entry points of the decode path (pq_decode_*, pq_score_keys) and the chunk merge kernel.
 // The attention and score-only kernel templates live in pq_decode_kernels.hpp.
+#include <mutex>
+
 #include "pq_decode_kernels.hpp"
 #include "pq_decode_roles.hpp"
 
@@ -8,6 +10,10 @@
 #ifndef PQ_USE_ROLES
 #define PQ_USE_ROLES 1
 #endif
+
+// Scratch of pq_decode_attention_static: the chunk partials live here instead of in a
+// caller-supplied workspace.  One copy per GPU, at its own address on each.
+static __device__ __align__(256) unsigned char scratch[PQ_STATIC_SCRATCH_BYTES];
 
 namespace pq {
 
@@ -179,6 +185,29 @@ AttentionKernel choose_attention_kernel(const pq_layout* l, int32_t v_bits, int6
   return AttentionKernel::kPartials;
 }
 
+// Device address of `scratch` on the current device (in host code the array's name is only a
+// handle for the lookup, not an address a kernel can use).  Resolved once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** ptr_out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return record_hip_error(e);
+  if (dev < 0 || dev >= kMaxDevices) return PQ_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return record_hip_error(e);
+    if (!p || (reinterpret_cast<uintptr_t>(p) & 255u)) return PQ_ERR_WORKSPACE;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr_out = g_scratch_ptr[dev];
+  return PQ_OK;
+}
+
 int check_decode_shape(const pq_layout* l, int32_t n_seqs, int32_t n_q_heads, int32_t max_seq_len) {
   if (!l || n_seqs <= 0 || n_q_heads <= 0 || max_seq_len <= 0) return PQ_ERR_INVALID_ARG;
   if (l->n_kv_heads <= 0 || n_q_heads % l->n_kv_heads != 0) return PQ_ERR_INVALID_ARG;
@@ -348,6 +377,25 @@ extern "C" int pq_decode_attention(const pq_layout* layout, const void* q, pq_dt
   if (st != PQ_OK) return st;
   return pq_decode_merge(layout, n_seqs, n_q_heads, seq_lens, max_seq_len, out, workspace, workspace_bytes,
                          hip_stream);
+}
+
+extern "C" int pq_decode_attention_static(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
+                                          int32_t n_q_heads, const void* codes_pool, const void* params_pool,
+                                          const void* v_pool, int32_t v_bits, const void* v_params_pool,
+                                          int64_t n_pool_pages, const int32_t* block_table,
+                                          int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
+                                          float sm_scale, float* out, float* scores, int64_t scores_stride,
+                                          const void* residual_keys, const int32_t* seq_order, void* hip_stream) {
+  const int st = check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len);
+  if (st != PQ_OK) return st;
+  const size_t need = pq_decode_workspace_bytes(layout, n_seqs, n_q_heads, max_seq_len);
+  if (need == 0 || need > static_cast<size_t>(PQ_STATIC_SCRATCH_BYTES)) return PQ_ERR_STATIC_LIMIT;
+  void* ws = nullptr;
+  const int sp = static_scratch(&ws);
+  if (sp != PQ_OK) return sp;
+  return pq_decode_attention(layout, q, q_dtype, n_seqs, n_q_heads, codes_pool, params_pool, v_pool, v_bits,
+                             v_params_pool, n_pool_pages, block_table, max_pages_per_seq, seq_lens, max_seq_len,
+                             sm_scale, out, scores, scores_stride, residual_keys, seq_order, ws, need, hip_stream);
 }
 
 extern "C" int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,

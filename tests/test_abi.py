@@ -112,6 +112,10 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     st = lib.pq_decode_partials(ctypes.byref(grouped), fake, 0, 1, 32, fake, fake, fake, 16, null, 4, fake, 1, fake, 128,
                                 0.1, null, 0, null, null, fake, 1 << 20, null)
     assert st == -2
+    # the allocation-free variant refuses, on the host, shapes beyond its static scratch array
+    st = lib.pq_decode_attention_static(ctypes.byref(lay), fake, 0, 512, 32, fake, fake, fake, 16, null, 4, fake, 128,
+                                        fake, 16384, 0.1, fake, null, 0, null, null, null)
+    assert st == -5 and "static" in pq.pq_strerror(st)
     assert lib.pq_order_sequences(null, 5, null, null) == -1 and lib.pq_order_sequences(null, 0, null, null) == 0
     assert pq.pq_version() >= 102
 
