@@ -50,65 +50,125 @@ def time_region(fn, n, torch):
     return start.elapsed_time(stop) / n
 
 
-def cpu_baseline(wl, lens, budget_s: float = 20.0):
-    """The oracle's decode (unpack -> dequantize -> dot -> softmax -> P.V, float64) timed on the
-    host for whole sequences of the same workload until about `budget_s` seconds are spent."""
+def _cpu_worker(wl, lens, my_seqs, budget_s, barrier, result_q):
+    """One host core's share of the oracle baseline: prepare its sequences (untimed: that is
+    prefill), wait for the others, then run the oracle's decode over them again and again until
+    `budget_s` seconds have passed.  Reports (scores computed, start, end) on the shared clock."""
     import numpy as np
     from threadpoolctl import threadpool_limits
 
     from oracle import attention, cache_format, polar
     from paper_2502_00527_amd import workloads as W
 
-    q = W.queries(wl)
     g = wl.group_tokens
-    scored = 0
-    spent = 0.0
-    n_done = 0
     with threadpool_limits(limits=1):
-        for s in range(wl.n_seqs):
+        q = W.queries(wl)
+        prepared = []
+        for s in my_seqs:
             L = int(lens[s])
             keys = W.keys_for_seq(wl, s, L)
-            enc = polar.encode_keys(keys, wl.r_bits, wl.t_bits, g, grouped_angles=wl.grouped_angles)   # not timed: prefill
+            enc = polar.encode_keys(keys, wl.r_bits, wl.t_bits, g, grouped_angles=wl.grouped_angles)
             codes, params = cache_format.pack_sequence(enc["a"], enc["c"], enc["scale"], enc["zero"],
                                                        wl.r_bits, wl.t_bits, g, enc.get("t_scale"), enc.get("t_zero"))
             n_pages = codes.shape[0]
             vals = np.zeros((n_pages * g, wl.n_kv_heads, wl.head_dim), np.float16)
             vals[:L] = W.values_for_seq(wl, s, L)
             v_pool = np.ascontiguousarray(vals.reshape(n_pages, g, wl.n_kv_heads, wl.head_dim).transpose(0, 2, 1, 3))
-            table = np.arange(n_pages, dtype=np.int32)[None, :]
-            t0 = time.perf_counter()
-            attention.decode_attention(q[s:s + 1], codes, params, v_pool, table, np.array([L]), wl.r_bits,
-                                       wl.t_bits, g, 1.0 / np.sqrt(wl.head_dim))
-            spent += time.perf_counter() - t0
-            scored += L * wl.n_q_heads
-            n_done += 1
-            if spent >= budget_s * 0.5 and spent / n_done * (n_done + 1) > budget_s:
+            prepared.append((s, L, codes, params, v_pool, np.arange(n_pages, dtype=np.int32)[None, :]))
+            del keys, enc, vals
+        barrier.wait()
+        t0 = time.perf_counter()
+        scored = 0
+        while True:
+            for s, L, codes, params, v_pool, table in prepared:
+                attention.decode_attention(q[s:s + 1], codes, params, v_pool, table, np.array([L]), wl.r_bits,
+                                           wl.t_bits, g, 1.0 / np.sqrt(wl.head_dim))
+                scored += L * wl.n_q_heads
+                if time.perf_counter() - t0 >= budget_s:
+                    break
+            if time.perf_counter() - t0 >= budget_s:
                 break
-    return {"value": scored / spent, "unit": "keys/s", "cores": 1, "kind": "oracle",
-            "sample": f"{n_done} of {wl.n_seqs} sequences of the same workload ({scored} scores, "
-                      f"{spent:.1f} s of NumPy float64 decode on one thread; encode not timed)"}
+        result_q.put((scored, t0, time.perf_counter()))
 
 
-def read_traffic_note(workload: str):
-    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc, if a
-    committed summary states it (profiles/decode_partials_<workload>_pmc.txt)."""
-    path = os.path.join(ROOT, "profiles", f"decode_partials_{workload}_pmc.txt")
+def cpu_baseline(wl, lens, budget_s: float = 10.0):
+    """The oracle's decode (unpack -> dequantize -> dot -> softmax -> P.V, float64) on the host
+    cores this process may use: one worker process per core (BLAS held to one thread each, so the
+    core count is exact), sequences of the same workload dealt round-robin, each worker decoding
+    its sequences repeatedly for about `budget_s` seconds.  Rate = all scores computed / wall time
+    between the first worker's start and the last one's end.  Must run before this process touches
+    the GPU: the workers are forked."""
+    import multiprocessing as mp
+
+    cores = len(os.sched_getaffinity(0))
+    n_workers = max(1, min(cores, wl.n_seqs))
+    ctx = mp.get_context("fork")
+    barrier = ctx.Barrier(n_workers)
+    result_q = ctx.Queue()
+    procs = []
+    for w in range(n_workers):
+        my = list(range(w, wl.n_seqs, n_workers))[:2]     # at most two sequences per worker: bounded set-up time
+        procs.append(ctx.Process(target=_cpu_worker, args=(wl, lens, my, budget_s, barrier, result_q)))
+        procs[-1].start()
+    got = [result_q.get() for _ in procs]
+    for p in procs:
+        p.join()
+    scored = sum(g[0] for g in got)
+    wall = max(g[2] for g in got) - min(g[1] for g in got)
+    used = sorted({s for w in range(n_workers) for s in list(range(w, wl.n_seqs, n_workers))[:2]})
+    return {"value": scored / wall, "unit": "keys/s", "cores": n_workers, "kind": "oracle",
+            "host_cores_available": cores,
+            "sample": f"{len(used)} of {wl.n_seqs} sequences of the same workload, decoded repeatedly by {n_workers} "
+                      f"worker processes (one per host core, one BLAS thread each) for {wall:.1f} s: {scored} scores "
+                      f"of NumPy float64 decode; encode not timed"}
+
+
+def read_traffic_note(workload: str, kernel: str):
+    """(HBM bytes per launch, source) of the dominant kernel as measured with rocprofv3 --pmc, if a
+    committed summary for this workload states it for the kernel that runs
+    (profiles/decode_partials_<workload>_pmc.txt); counters cannot be read inside a timed run, so
+    this is a recorded figure, not one measured by this process."""
+    rel = os.path.join("profiles", f"decode_partials_{workload}_pmc.txt")
     try:
-        with open(path) as f:
-            for line in f:
-                if line.startswith("traffic_bytes_per_launch:"):
-                    return int(float(line.split(":", 1)[1].split()[0]))
+        with open(os.path.join(ROOT, rel)) as f:
+            text = f.read()
     except OSError:
-        pass
-    return None
+        return None, None
+    if kernel not in text:
+        return None, None
+    for line in text.splitlines():
+        if line.startswith("traffic_bytes_per_launch:"):
+            return int(float(line.split(":", 1)[1].split()[0])), rel + " (recorded with rocprofv3 --pmc, not measured in this run)"
+    return None, None
+
+
+def preheat(fn, torch, min_busy_ms: float = 60.0, window: int = 20, tol: float = 0.02, max_busy_ms: float = 2000.0):
+    """Untimed steps until the device runs at its steady clocks: windows of `window` steps until at
+    least `min_busy_ms` of load have passed and two consecutive windows agree within `tol` (an idle
+    device takes some tens of milliseconds of load to raise its clocks).  Returns what was done."""
+    busy, n, first, prev = 0.0, 0, None, None
+    while True:
+        ms = time_region(fn, window, torch)
+        busy += ms * window
+        n += window
+        if first is None:
+            first = ms
+        if busy >= min_busy_ms and prev is not None and abs(ms - prev) <= tol * prev:
+            break
+        if busy >= max_busy_ms:
+            break
+        prev = ms
+    return {"steps": n, "busy_ms": busy, "first_window_ms_per_step": first, "last_window_ms_per_step": ms}
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=200,
-                    help="untimed steps; the device needs ~150 launches (~35 ms) of load to reach its steady clocks")
+    ap.add_argument("--warmup", type=int, default=10, help="untimed steps before anything else")
+    ap.add_argument("--no-preheat", action="store_true",
+                    help="skip the disclosed, untimed pre-heat that follows the warm-up steps (an idle device needs "
+                         "some tens of milliseconds of load to reach its steady clocks; see `preheat` in the output)")
     ap.add_argument("--workload", default="gqa", choices=["gqa", "mha", "long33", "ragged", "tiny"])
     ap.add_argument("--v-bits", type=int, default=16, choices=[16, 4, 2],
                     help="value precision: 16 = fp16 values (the headline configuration), 4 / 2 = token-wise quantized")
@@ -120,7 +180,8 @@ def main() -> int:
     ap.add_argument("--no-seq-order", action="store_true",
                     help="ragged batches: do not pass the longest-first start order to the decode call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-budget", type=float, default=20.0)
+    ap.add_argument("--cpu-budget", type=float, default=10.0,
+                    help="seconds every host core spends in the oracle's decode")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1",
@@ -128,17 +189,29 @@ def main() -> int:
         return 2
 
     import numpy as np
+
+    from paper_2502_00527_amd import workloads as W
+
+    wl = W.WORKLOADS[args.workload]
+    if args.grouped_angles:
+        wl = wl.scaled(grouped_angles=True)
+
+    # The oracle on the host cores comes first: its worker processes are forked, which has to
+    # happen before this process initialises the GPU.
+    cpu = None
+    if not args.no_cpu_baseline:
+        print("[bench] oracle baseline on the host cores ...", file=sys.stderr, flush=True)
+        t0 = time.time()
+        cpu = cpu_baseline(wl, W.seq_lengths(wl), args.cpu_budget)
+        print(f"[bench] oracle baseline done in {time.time() - t0:.1f} s on {cpu['cores']} cores", file=sys.stderr, flush=True)
+
     import torch
 
     import paper_2502_00527_amd as pq
-    from paper_2502_00527_amd import workloads as W
     from paper_2502_00527_amd.cache import build_device_cache
 
     pq.load_library()          # raises if libpolarquant.so is not built: there is no fallback
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    wl = W.WORKLOADS[args.workload]
-    if args.grouped_angles:
-        wl = wl.scaled(grouped_angles=True)
     t0 = time.time()
     cache = build_device_cache(wl, v_bits=args.v_bits,
                                progress=lambda s: print(f"[bench] encoded sequence {s + 1}/{wl.n_seqs}",
@@ -184,15 +257,30 @@ def main() -> int:
         pq.pq_decode_merge(cache.layout, wl.n_seqs, wl.n_q_heads, cache.seq_lens, cache.max_seq_len, out,
                            cache.workspace)
 
+    # buffers of the read-stream probe, allocated now so that nothing idles the device between the
+    # timed regions below
+    probe = torch.empty(2 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+    sink = torch.zeros(64, dtype=torch.int32, device="cuda:0")
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # Disclosed pre-heat, untimed and independent of --warmup: an idle device runs its first tens of
+    # milliseconds of load at lower clocks (the first window's time is reported as the cold figure).
+    heat = None if args.no_preheat else preheat(step, torch)
     t_start = time.perf_counter()
     ms_step = time_region(step, args.steps, torch)
     wall = time.perf_counter() - t_start
-    # the dominant kernel alone, same launch configuration, same stream
+    # the dominant kernel alone, same launch configuration, same stream, same clock state
     ms_partials = time_region(partials_only, args.steps, torch)
     ms_merge = time_region(merge_only, args.steps, torch)
+    # what this device streams with bare non-temporal 128-bit loads (context for the roofline
+    # fraction), timed right behind the kernel so that both see the same clocks
+    for _ in range(5):
+        pq.pq_probe_read_stream(probe, sink)
+    ms_probe = time_region(lambda: pq.pq_probe_read_stream(probe, sink), 20, torch)
+    read_stream_gbps = probe.numel() / (ms_probe * 1e-3) / 1e9
+    del probe
 
     # the query-key product alone (pq_score_keys): the one operation the paper itself times
     # (Section 5.2, batch 8); context beside the headline, not part of `value`
@@ -206,6 +294,8 @@ def main() -> int:
 
         for _ in range(args.warmup):
             qk_only()
+        if not args.no_preheat:
+            preheat(qk_only, torch, min_busy_ms=20.0)
         ms_qk = time_region(qk_only, args.steps, torch)
         n_scores = int(lens[:8].astype(np.int64).sum()) * wl.n_q_heads
         qk = {"entry_point": "pq_score_keys", "batch": 8, "ms_per_call": ms_qk,
@@ -232,6 +322,8 @@ def main() -> int:
 
         for _ in range(10):
             encode_only()
+        if not args.no_preheat:
+            preheat(encode_only, torch, min_busy_ms=20.0)
         ms_enc = time_region(encode_only, 50, torch)
         enc_bytes = keys.numel() * keys.element_size() + e_codes.numel() + e_params.numel()
         enc = {"entry_point": "pq_encode_keys", "tokens": n_tok, "kv_heads": pre.n_kv_heads, "ms_per_call": ms_enc,
@@ -240,15 +332,8 @@ def main() -> int:
                "note": "exactly rounded fp32 radius chain and exact angle classification; not HBM-bound"}
         del keys, e_codes, e_params
 
-    # what this device streams with bare non-temporal 128-bit loads (context for the roofline fraction)
-    probe = torch.empty(2 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
-    sink = torch.zeros(64, dtype=torch.int32, device="cuda:0")
-    for _ in range(3):
-        pq.pq_probe_read_stream(probe, sink)
-    ms_probe = time_region(lambda: pq.pq_probe_read_stream(probe, sink), 20, torch)
-    read_stream_gbps = probe.numel() / (ms_probe * 1e-3) / 1e9
-    del probe
-
+    kernel = pq.pq_decode_kernel_name(cache.layout, wl.n_seqs, wl.n_q_heads, cache.max_seq_len, args.v_bits)
+    traffic, traffic_source = read_traffic_note(wl.name, kernel) if args.v_bits == 16 and not wl.grouped_angles else (None, None)
     keys_scored = int(lens.astype(np.int64).sum()) * wl.n_q_heads
     alg_bytes = algorithmic_bytes(wl, lens, args.v_bits)
     achieved = alg_bytes / (ms_partials * 1e-3) / 1e9
@@ -268,23 +353,23 @@ def main() -> int:
                    "keys_scored_per_step": keys_scored,
                    "kv_tokens_per_step": int(lens.astype(np.int64).sum()) * wl.n_kv_heads},
         "roofline": {"bound": "hbm",
-                     "kernel": "pq_decode_roles_kernel" if (args.v_bits == 16 and not wl.grouped_angles)
-                     else "pq_decode_partials_kernel", "achieved": achieved,
+                     "kernel": kernel, "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": read_traffic_note(wl.name) if args.v_bits == 16 and not wl.grouped_angles else None,
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "algorithmic_bytes": alg_bytes,
                      "ms_per_launch": ms_partials, "ms_merge_kernel": ms_merge,
                      "read_stream_GBps": read_stream_gbps,
                      "frac_of_read_stream": achieved / read_stream_gbps,
                      "whole_step_GBps": alg_bytes / (ms_step * 1e-3) / 1e9},
         "wall_s_timed_region": wall,
+        "preheat": heat,
     }
     if qk is not None:
         result["qk_only"] = qk
     if enc is not None:
         result["encode"] = enc
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, lens, args.cpu_budget)
+    if cpu is not None:
+        result["cpu_baseline"] = cpu
     print(json.dumps(result), flush=True)
     return 0
 
