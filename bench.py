@@ -177,8 +177,6 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=4,
                     help="independent copies of the packed cache that successive steps rotate over, so that the "
                          "256 MB memory-side cache cannot serve a step from the previous step's reads")
-    ap.add_argument("--no-seq-order", action="store_true",
-                    help="ragged batches: do not pass the longest-first start order to the decode call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=10.0,
                     help="seconds every host core spends in the oracle's decode")
@@ -220,11 +218,6 @@ def main() -> int:
     print(f"[bench] inputs ready in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
     lens = cache.lens
     out = torch.empty((wl.n_seqs, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device="cuda:0")
-    if wl.min_len != wl.max_len and not args.no_seq_order:
-        # ragged batch: start the longest sequences first.  The order is computed once, outside the
-        # timed region: a decode step lengthens every sequence by one token, which keeps it valid.
-        cache.seq_order = torch.empty(wl.n_seqs, dtype=torch.int32, device="cuda:0")
-        pq.pq_order_sequences(cache.seq_lens, cache.seq_order)
 
     # N copies of the pools in one N-times larger pool; copy k is reached through block table k
     n_copies = max(1, args.copies)
@@ -251,7 +244,7 @@ def main() -> int:
         c = next_view()
         pq.pq_decode_partials(c.layout, c.q, c.codes, c.params, c.values, c.block_table,
                               c.seq_lens, c.max_seq_len, c.sm_scale, c.workspace,
-                              v_bits=c.v_bits, v_params=c.v_params, seq_order=c.seq_order)
+                              v_bits=c.v_bits, v_params=c.v_params)
 
     def merge_only():
         pq.pq_decode_merge(cache.layout, wl.n_seqs, wl.n_q_heads, cache.seq_lens, cache.max_seq_len, out,
@@ -271,9 +264,13 @@ def main() -> int:
     t_start = time.perf_counter()
     ms_step = time_region(step, args.steps, torch)
     wall = time.perf_counter() - t_start
-    # the dominant kernel alone, same launch configuration, same stream, same clock state
-    ms_partials = time_region(partials_only, args.steps, torch)
-    ms_merge = time_region(merge_only, args.steps, torch)
+    # the dominant kernel alone, same launch configuration, same stream, same clock state.  The
+    # role-specialised kernel merges inside the kernel: the step IS that one kernel, timed again
+    # here in a region of its own; the other kernels are followed by a separate merge kernel.
+    kernel = pq.pq_decode_kernel_name(cache.layout, wl.n_seqs, wl.n_q_heads, cache.max_seq_len, args.v_bits)
+    one_kernel_step = kernel == "pq_decode_roles_kernel"
+    ms_partials = time_region(step if one_kernel_step else partials_only, args.steps, torch)
+    ms_merge = 0.0 if one_kernel_step else time_region(merge_only, args.steps, torch)
     # what this device streams with bare non-temporal 128-bit loads (context for the roofline
     # fraction), timed right behind the kernel so that both see the same clocks
     for _ in range(5):
@@ -332,7 +329,6 @@ def main() -> int:
                "note": "exactly rounded fp32 radius chain and exact angle classification; not HBM-bound"}
         del keys, e_codes, e_params
 
-    kernel = pq.pq_decode_kernel_name(cache.layout, wl.n_seqs, wl.n_q_heads, cache.max_seq_len, args.v_bits)
     traffic, traffic_source = read_traffic_note(wl.name, kernel) if args.v_bits == 16 and not wl.grouped_angles else (None, None)
     keys_scored = int(lens.astype(np.int64).sum()) * wl.n_q_heads
     alg_bytes = algorithmic_bytes(wl, lens, args.v_bits)
@@ -349,7 +345,7 @@ def main() -> int:
                                f"head_dim {wl.head_dim}, context {wl.min_len}..{wl.max_len}, r{wl.r_bits}/t{wl.t_bits}, "
                                f"group {wl.group_tokens}, {'grouped' if wl.grouped_angles else 'uniform'} angle quantizer, {'fp16' if args.v_bits == 16 else str(args.v_bits) + '-bit'} values, "
                                f"RoPE base {wl.rope_base:g}",
-                   "cache_copies_rotated": n_copies, "longest_first_order": cache.seq_order is not None,
+                   "cache_copies_rotated": n_copies,
                    "keys_scored_per_step": keys_scored,
                    "kv_tokens_per_step": int(lens.astype(np.int64).sum()) * wl.n_kv_heads},
         "roofline": {"bound": "hbm",
@@ -357,7 +353,7 @@ def main() -> int:
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": traffic, "traffic_source": traffic_source,
                      "algorithmic_bytes": alg_bytes,
-                     "ms_per_launch": ms_partials, "ms_merge_kernel": ms_merge,
+                     "ms_per_launch": ms_partials, "ms_merge_kernel": ms_merge, "merge_in_kernel": one_kernel_step,
                      "read_stream_GBps": read_stream_gbps,
                      "frac_of_read_stream": achieved / read_stream_gbps,
                      "whole_step_GBps": alg_bytes / (ms_step * 1e-3) / 1e9},

@@ -192,14 +192,6 @@ int pq_encode_values(const pq_layout* layout, int32_t v_bits, const void* values
  *                 plain dot products; packed pages then hold complete groups only.  NULL: the
  *                 incomplete group, if any, is read from its packed page (as pq_encode_keys
  *                 writes it).  Values always come from the value pool.
- *   seq_order     optional device int32 [n_seqs]: a permutation of 0 .. n_seqs-1 naming the order
- *                 in which the sequences' work is started (NULL: as numbered).  Results do not
- *                 depend on it.  In a batch of very different lengths, starting the longest
- *                 sequences first shortens the launch (measured: 7 % on 64 sequences of 1K-16K
- *                 tokens); pq_order_sequences writes such an order, and since every decode step
- *                 lengthens all sequences by one token it stays valid while the batch's membership
- *                 does.  Entries outside [0, n_seqs) are skipped, so a wrong array can leave
- *                 sequences out but cannot cause an out-of-range access.
  *   workspace     device, >= pq_decode_workspace_bytes(layout, n_seqs, n_q_heads, max_seq_len),
  *                 256-byte aligned; contents are scratch
  *
@@ -211,7 +203,7 @@ int pq_decode_attention(const pq_layout* layout, const void* q, pq_dtype q_dtype
                         int64_t n_pool_pages, const int32_t* block_table,
                         int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
                         float sm_scale, float* out, float* scores, int64_t scores_stride,
-                        const void* residual_keys, const int32_t* seq_order, void* workspace,
+                        const void* residual_keys, void* workspace,
                         size_t workspace_bytes, void* hip_stream);
 
 /*
@@ -239,7 +231,7 @@ int pq_decode_attention_static(const pq_layout* layout, const void* q, pq_dtype 
                                int64_t n_pool_pages, const int32_t* block_table,
                                int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
                                float sm_scale, float* out, float* scores, int64_t scores_stride,
-                               const void* residual_keys, const int32_t* seq_order, void* hip_stream);
+                               const void* residual_keys, void* hip_stream);
 
 /*
  * The two stages of pq_decode_attention, callable on their own (the benchmark
@@ -257,7 +249,7 @@ int pq_decode_partials(const pq_layout* layout, const void* q, pq_dtype q_dtype,
                        int64_t n_pool_pages, const int32_t* block_table,
                        int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
                        float sm_scale, float* scores, int64_t scores_stride, const void* residual_keys,
-                       const int32_t* seq_order, void* workspace, size_t workspace_bytes, void* hip_stream);
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
 int pq_decode_merge(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
                     const int32_t* seq_lens, int32_t max_seq_len, float* out,
                     const void* workspace, size_t workspace_bytes, void* hip_stream);
@@ -270,13 +262,6 @@ int pq_decode_merge(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
  */
 const char* pq_decode_kernel_name(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
                                   int32_t max_seq_len, int32_t v_bits);
-
-/*
- * pq_order_sequences -- writes into order_out (device int32 [n_seqs]) the sequence indices sorted
- * by decreasing seq_lens (ties by index), for the seq_order argument of the decode calls.  One small
- * kernel; batches of more than 2048 sequences get the identity order.
- */
-int pq_order_sequences(const int32_t* seq_lens, int32_t n_seqs, int32_t* order_out, void* hip_stream);
 
 /*
  * pq_append_keys -- one decode step's new key per sequence.  Methods of this kind keep the most

@@ -23,7 +23,7 @@ __all__ = [
     "pq_values_bytes_per_page", "pq_decode_workspace_bytes", "pq_encode_keys",
     "pq_decode_attention", "pq_decode_partials", "pq_decode_merge", "pq_score_keys", "pq_append_keys",
     "pq_vq_bytes_per_page", "pq_vq_params_bytes_per_page", "pq_encode_values",
-    "pq_probe_read_stream", "pq_order_sequences", "pq_decode_kernel_name",
+    "pq_probe_read_stream", "pq_decode_kernel_name",
     "pq_decode_attention_static", "PQ_STATIC_SCRATCH_BYTES",
 ]
 
@@ -63,13 +63,13 @@ _SIGNATURES = {
                                c_void_p, c_int64, c_void_p]),
     "pq_decode_attention": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                     c_int32, c_void_p, c_int64, c_void_p, c_int32, c_void_p, c_int32, c_float, c_void_p,
-                                    c_void_p, c_int64, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+                                    c_void_p, c_int64, c_void_p, c_void_p, c_size_t, c_void_p]),
     "pq_decode_attention_static": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                            c_int32, c_void_p, c_int64, c_void_p, c_int32, c_void_p, c_int32, c_float,
-                                           c_void_p, c_void_p, c_int64, c_void_p, c_void_p, c_void_p]),
+                                           c_void_p, c_void_p, c_int64, c_void_p, c_void_p]),
     "pq_decode_partials": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                    c_int32, c_void_p, c_int64, c_void_p, c_int32, c_void_p, c_int32, c_float, c_void_p,
-                                   c_int64, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+                                   c_int64, c_void_p, c_void_p, c_size_t, c_void_p]),
     "pq_vq_bytes_per_page": (c_size_t, [_LP, c_int32]),
     "pq_vq_params_bytes_per_page": (c_size_t, [_LP]),
     "pq_encode_values": (c_int, [_LP, c_int32, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p,
@@ -80,7 +80,6 @@ _SIGNATURES = {
                                 c_void_p]),
     "pq_score_keys": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_int64, c_void_p,
                               c_int32, c_void_p, c_int32, c_void_p, c_int64, c_void_p, c_void_p]),
-    "pq_order_sequences": (c_int, [c_void_p, c_int32, c_void_p, c_void_p]),
     "pq_decode_kernel_name": (ctypes.c_char_p, [_LP, c_int32, c_int32, c_int32, c_int32]),
     "pq_probe_read_stream": (c_int, [c_void_p, c_size_t, c_void_p, c_void_p]),
 }
@@ -189,25 +188,6 @@ def pq_encode_keys(layout: Layout, keys, page_ids, codes_pool, params_pool) -> N
     _check(st, "pq_encode_keys")
 
 
-def _order_ptr(seq_order, n_seqs):
-    import torch
-    if seq_order is None:
-        return None
-    if seq_order.numel() != n_seqs:
-        raise PolarQuantError("seq_order must have one entry per sequence")
-    return _dev_ptr(seq_order, "seq_order", (torch.int32,))
-
-
-def pq_order_sequences(seq_lens, order_out) -> None:
-    """order_out (int32 [n_seqs], device) := sequence indices by decreasing length."""
-    import torch
-    if order_out.numel() != seq_lens.numel():
-        raise PolarQuantError("order_out must have one entry per sequence")
-    st = load_library().pq_order_sequences(_dev_ptr(seq_lens, "seq_lens", (torch.int32,)), seq_lens.numel(),
-                                           _dev_ptr(order_out, "order_out", (torch.int32,)), _stream())
-    _check(st, "pq_order_sequences")
-
-
 def _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens, v_bits=16, v_params=None):
     import torch
     if q.dim() != 3 or q.shape[2] != layout.head_dim:
@@ -231,7 +211,7 @@ def _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_
 
 def pq_decode_attention(layout: Layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens,
                         max_seq_len: int, sm_scale: float, out, workspace, scores=None, residual=None,
-                        v_bits: int = 16, v_params=None, seq_order=None) -> None:
+                        v_bits: int = 16, v_params=None) -> None:
     """One decode step per sequence; see include/polarquant.h.  `out` fp32 [n_seqs, n_q_heads, d];
     `scores` optional fp32 [n_seqs, n_q_heads, stride >= max_seq_len]; `workspace` a uint8 device
     tensor of at least pq_decode_workspace_bytes(...) bytes."""
@@ -244,14 +224,13 @@ def pq_decode_attention(layout: Layout, q, codes_pool, params_pool, v_pool, bloc
         None if scores is None else _dev_ptr(scores, "scores", (torch.float32,)),
         0 if scores is None else scores.shape[-1],
         None if residual is None else _dev_ptr(residual, "residual", (torch.float16,)),
-        _order_ptr(seq_order, c["n_seqs"]),
         _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream())
     _check(st, "pq_decode_attention")
 
 
 def pq_decode_attention_static(layout: Layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens,
                                max_seq_len: int, sm_scale: float, out, scores=None, residual=None,
-                               v_bits: int = 16, v_params=None, seq_order=None) -> None:
+                               v_bits: int = 16, v_params=None) -> None:
     """pq_decode_attention without a workspace argument (the library's static scratch array)."""
     import torch
     c = _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens, v_bits, v_params)
@@ -262,13 +241,13 @@ def pq_decode_attention_static(layout: Layout, q, codes_pool, params_pool, v_poo
         None if scores is None else _dev_ptr(scores, "scores", (torch.float32,)),
         0 if scores is None else scores.shape[-1],
         None if residual is None else _dev_ptr(residual, "residual", (torch.float16,)),
-        _order_ptr(seq_order, c["n_seqs"]), _stream())
+        _stream())
     _check(st, "pq_decode_attention_static")
 
 
 def pq_decode_partials(layout: Layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens,
                        max_seq_len: int, sm_scale: float, workspace, scores=None, residual=None,
-                       v_bits: int = 16, v_params=None, seq_order=None) -> None:
+                       v_bits: int = 16, v_params=None) -> None:
     import torch
     c = _decode_common(layout, q, codes_pool, params_pool, v_pool, block_table, seq_lens, v_bits, v_params)
     st = load_library().pq_decode_partials(
@@ -277,7 +256,6 @@ def pq_decode_partials(layout: Layout, q, codes_pool, params_pool, v_pool, block
         None if scores is None else _dev_ptr(scores, "scores", (torch.float32,)),
         0 if scores is None else scores.shape[-1],
         None if residual is None else _dev_ptr(residual, "residual", (torch.float16,)),
-        _order_ptr(seq_order, c["n_seqs"]),
         _dev_ptr(workspace, "workspace"), workspace.numel() * workspace.element_size(), _stream())
     _check(st, "pq_decode_partials")
 

@@ -34,7 +34,6 @@ class DeviceCache:
     q: torch.Tensor                  # [S, Hq, d]
     workspace: torch.Tensor
     max_seq_len: int
-    seq_order: Optional[torch.Tensor] = None   # int32 [S]: start order of the sequences' work (None: as numbered)
 
     @property
     def sm_scale(self) -> float:
@@ -47,7 +46,7 @@ class DeviceCache:
                               device=self.q.device)
         pq_decode_attention(self.layout, self.q, self.codes, self.params, self.values, self.block_table,
                             self.seq_lens, self.max_seq_len, self.sm_scale, out, self.workspace, scores, residual,
-                            self.v_bits, self.v_params, self.seq_order)
+                            self.v_bits, self.v_params)
         return out
 
 

@@ -1,5 +1,6 @@
 // Host entry points of the decode path (pq_decode_*, pq_score_keys) and the chunk merge kernel.
 // The attention and score-only kernel templates live in pq_decode_kernels.hpp.
+#include <algorithm>
 #include <mutex>
 
 #include "pq_decode_kernels.hpp"
@@ -87,29 +88,6 @@ __global__ __launch_bounds__(kMergeThreads) void pq_decode_merge_kernel(
   }
 }
 
-// order[rank] = index of the sequence with `rank` longer ones before it (ties: lower index first).
-// One work-group; every thread ranks the sequences t, t + 1024, ... against all lengths in LDS.
-constexpr int kOrderMax = 2048;
-__global__ __launch_bounds__(1024) void pq_order_kernel(const int32_t* __restrict__ seq_lens, int32_t n_seqs,
-                                                        int32_t* __restrict__ order) {
-  __shared__ int32_t len_s[kOrderMax];
-  for (int i = threadIdx.x; i < n_seqs; i += blockDim.x) {
-    if (n_seqs > kOrderMax) order[i] = i;
-    else len_s[i] = seq_lens[i];
-  }
-  if (n_seqs > kOrderMax) return;
-  __syncthreads();
-  for (int i = threadIdx.x; i < n_seqs; i += blockDim.x) {
-    const int32_t mine = len_s[i];
-    int rank = 0;
-    for (int j = 0; j < n_seqs; ++j) {
-      const int32_t other = len_s[j];
-      rank += (other > mine) || (other == mine && j < i);
-    }
-    order[rank] = i;
-  }
-}
-
 template <int RB, int TB>
 hipError_t launch_scores(int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st) {
 #define PQ_LAUNCH_SCORES(GG)                                                                            \
@@ -124,20 +102,71 @@ hipError_t launch_scores(int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hi
   return hipGetLastError();
 }
 
+// Which attention kernel a launch gets.  The role-specialised kernel, whose work-groups share
+// the launch's pages out evenly and merge in the kernel, serves fp16 values with the uniform
+// angle grid when there is work for at least 256 work-groups; smaller launches stay with the
+// kernel whose four wavefronts share a chunk's pages four ways (measured: 9 against 12 us for one
+// head over 4096 tokens).
+enum class AttentionKernel { kPartials, kRoles };
+constexpr int kComputeUnits = 256;           // MI355X
+
+#ifndef PQ_BALANCED_MIN_PAGES
+#define PQ_BALANCED_MIN_PAGES 4
+#endif
+#ifndef PQ_BALANCED_GROUPS
+#define PQ_BALANCED_GROUPS (kComputeUnits * kRoleGroupsPerCu)
+#endif
+constexpr int kBalancedMinPages = PQ_BALANCED_MIN_PAGES;   // smallest share of a work-group: two pages per wavefront pair
+#ifndef PQ_BALANCED_UNIT_COST
+#define PQ_BALANCED_UNIT_COST 2
+#endif
+constexpr int kBalancedUnitCost = PQ_BALANCED_UNIT_COST;   // pages' worth of time to start on a (sequence, KV head)
+constexpr int kBalancedMaxSeqs = 4096;       // every work-group scans all sequence lengths
+
+// Work-groups of a balanced launch: all that are resident at once (3 per compute unit), fewer if
+// the shape cannot have kBalancedMinPages pages for each.
+int balanced_groups(const pq_layout* l, int32_t n_seqs, int32_t max_seq_len) {
+  const int64_t max_pages = (static_cast<int64_t>(max_seq_len) + kGroup - 1) / kGroup;
+  const int64_t bound = static_cast<int64_t>(n_seqs) * l->n_kv_heads * max_pages;   // pages x KV heads, at most
+  return static_cast<int>(std::min<int64_t>(PQ_BALANCED_GROUPS,
+                                            (bound + kBalancedMinPages - 1) / kBalancedMinPages));
+}
+
+AttentionKernel choose_attention_kernel(const pq_layout* l, int32_t v_bits, int32_t n_seqs, int32_t max_seq_len) {
+  const int64_t max_pages = (static_cast<int64_t>(max_seq_len) + kGroup - 1) / kGroup;
+  const int64_t bound = static_cast<int64_t>(n_seqs) * l->n_kv_heads * (max_pages + kBalancedUnitCost);
+  if (PQ_USE_ROLES && l->angle_quantizer == PQ_ANGLE_UNIFORM && v_bits == 16 && n_seqs <= kBalancedMaxSeqs &&
+      bound < (int64_t{1} << 31) && balanced_groups(l, n_seqs, max_seq_len) >= 256)
+    return AttentionKernel::kRoles;
+  return AttentionKernel::kPartials;
+}
+
+// The caller's workspace holds either the chunk partials of a grid launch ([seq][q head][chunk])
+// or, for a balanced launch, one partial per segment slot ([slot][head of the group], slots =
+// work-groups + units) and the units' arrival words.  Its size covers both.
 struct Workspace {
   float* acc;
   float* ml;
+  uint64_t* arrivals;
   size_t bytes;
 };
 
-Workspace carve_workspace(void* base, int32_t n_seqs, int32_t n_q_heads, int32_t n_chunks) {
-  const size_t slots = static_cast<size_t>(n_seqs) * n_q_heads * n_chunks;
-  const size_t acc_bytes = (slots * kHeadDim * sizeof(float) + 255) & ~static_cast<size_t>(255);
-  const size_t ml_bytes = (slots * 2 * sizeof(float) + 255) & ~static_cast<size_t>(255);
+size_t round256(size_t n) { return (n + 255) & ~static_cast<size_t>(255); }
+
+Workspace carve_workspace(void* base, const pq_layout* l, int32_t n_seqs, int32_t n_q_heads, int32_t max_seq_len) {
+  const ChunkPlan plan = plan_chunks(n_seqs, l->n_kv_heads, max_seq_len);
+  const size_t units = static_cast<size_t>(n_seqs) * l->n_kv_heads;
+  const size_t grid_slots = static_cast<size_t>(n_seqs) * n_q_heads * plan.n_chunks;
+  const size_t balanced_slots = (static_cast<size_t>(balanced_groups(l, n_seqs, max_seq_len)) + units) * (n_q_heads / l->n_kv_heads);
+  const size_t slots = std::max(grid_slots, balanced_slots);
+  const size_t acc_bytes = round256(slots * kHeadDim * sizeof(float));
+  const size_t ml_bytes = round256(slots * 2 * sizeof(float));
   Workspace w;
   w.acc = static_cast<float*>(base);
   w.ml = reinterpret_cast<float*>(static_cast<uint8_t*>(base) + acc_bytes);
-  w.bytes = acc_bytes + ml_bytes;
+  w.arrivals = reinterpret_cast<uint64_t*>(static_cast<uint8_t*>(base) + acc_bytes + ml_bytes);
+  const size_t words = units + static_cast<size_t>(balanced_groups(l, n_seqs, max_seq_len)) + units;   // per unit, per segment slot
+  w.bytes = acc_bytes + ml_bytes + round256(words * sizeof(uint64_t));
   return w;
 }
 
@@ -172,17 +201,6 @@ void fill_angle_tables(DecodeArgs& a, int t_bits) {
     a.cos_tab[s] = s < nb ? static_cast<float>(cos(th)) : 0.f;
     a.sin_tab[s] = s < nb ? static_cast<float>(sin(th)) : 0.f;
   }
-}
-
-// Which attention kernel a launch gets.  The role-specialised kernel serves fp16 values with the
-// uniform angle grid when the launch has at least 256 work-groups; launches of a few work-groups
-// stay with the kernel whose four wavefronts share a chunk's pages four ways (measured: 9
-// against 12 us for one head over 4096 tokens).
-enum class AttentionKernel { kPartials, kRoles };
-AttentionKernel choose_attention_kernel(const pq_layout* l, int32_t v_bits, int64_t n_groups) {
-  if (PQ_USE_ROLES && l->angle_quantizer == PQ_ANGLE_UNIFORM && v_bits == 16 && n_groups >= 256)
-    return AttentionKernel::kRoles;
-  return AttentionKernel::kPartials;
 }
 
 // Device address of `scratch` on the current device (in host code the array's name is only a
@@ -228,18 +246,20 @@ using namespace pq;
 extern "C" size_t pq_decode_workspace_bytes(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
                                             int32_t max_seq_len) {
   if (check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len) != PQ_OK) return 0;
-  const ChunkPlan plan = plan_chunks(n_seqs, layout->n_kv_heads, max_seq_len);
-  return carve_workspace(nullptr, n_seqs, n_q_heads, plan.n_chunks).bytes;
+  return carve_workspace(nullptr, layout, n_seqs, n_q_heads, max_seq_len).bytes;
 }
 
-extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
-                                  int32_t n_q_heads, const void* codes_pool, const void* params_pool,
-                                  const void* v_pool, int32_t v_bits, const void* v_params_pool,
-                                  int64_t n_pool_pages, const int32_t* block_table,
-                                  int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
-                                  float sm_scale, float* scores, int64_t scores_stride,
-                                  const void* residual_keys, const int32_t* seq_order, void* workspace,
-                                  size_t workspace_bytes, void* hip_stream) {
+namespace pq {
+namespace {
+
+// Everything the decode entry points have in common: argument checks, kernel arguments, and the
+// launches.  `out` null = only the first stage of the two-stage (grid) path, the chunk partials.
+int decode_launch(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs, int32_t n_q_heads,
+                  const void* codes_pool, const void* params_pool, const void* v_pool, int32_t v_bits,
+                  const void* v_params_pool, int64_t n_pool_pages, const int32_t* block_table,
+                  int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len, float sm_scale,
+                  float* out, float* scores, int64_t scores_stride, const void* residual_keys,
+                  void* workspace, size_t workspace_bytes, void* hip_stream) {
   const int st = check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len);
   if (st != PQ_OK) return st;
   if (!q || !codes_pool || !params_pool || !v_pool || !block_table || !seq_lens) return PQ_ERR_INVALID_ARG;
@@ -249,16 +269,25 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
   if (need_pages > max_pages_per_seq) return PQ_ERR_INVALID_ARG;
   if (scores && scores_stride < max_seq_len) return PQ_ERR_INVALID_ARG;
   if (!isfinite(sm_scale)) return PQ_ERR_INVALID_ARG;
-  if (reinterpret_cast<uintptr_t>(residual_keys) & 15u) return PQ_ERR_INVALID_ARG;
   if (v_bits != 16 && v_bits != 4 && v_bits != 2) return PQ_ERR_UNSUPPORTED;
   if (v_bits != 16 && !v_params_pool) return PQ_ERR_INVALID_ARG;
+  // every pool is read with 128-bit loads
+  if ((reinterpret_cast<uintptr_t>(codes_pool) | reinterpret_cast<uintptr_t>(params_pool) |
+       reinterpret_cast<uintptr_t>(v_pool) | reinterpret_cast<uintptr_t>(residual_keys)) & 15u)
+    return PQ_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(v_params_pool) | reinterpret_cast<uintptr_t>(block_table) |
+       reinterpret_cast<uintptr_t>(seq_lens)) & 3u)
+    return PQ_ERR_INVALID_ARG;
+  const int rt = layout->r_bits * 10 + layout->t_bits;
+  const bool grouped = layout->angle_quantizer == PQ_ANGLE_GROUPED;
+  if ((grouped || v_bits != 16) && rt != 44 && rt != 33) return PQ_ERR_UNSUPPORTED;   // built for the two main settings
 
-  const ChunkPlan plan = plan_chunks(n_seqs, layout->n_kv_heads, max_seq_len);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return PQ_ERR_WORKSPACE;
-  const Workspace ws = carve_workspace(workspace, n_seqs, n_q_heads, plan.n_chunks);
+  const Workspace ws = carve_workspace(workspace, layout, n_seqs, n_q_heads, max_seq_len);
   if (workspace_bytes < ws.bytes) return PQ_ERR_WORKSPACE;
+  const ChunkPlan plan = plan_chunks(n_seqs, layout->n_kv_heads, max_seq_len);
 
-  DecodeArgs a;
+  DecodeArgs a = {};
   a.q = q;
   a.codes = static_cast<const uint8_t*>(codes_pool);
   a.params = static_cast<const uint32_t*>(params_pool);
@@ -267,11 +296,14 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
   a.v_params = static_cast<const uint32_t*>(v_params_pool);
   a.block_table = block_table;
   a.seq_lens = seq_lens;
-  a.seq_order = seq_order;
   a.n_seqs = n_seqs;
   a.scores = scores;
   a.ws_acc = ws.acc;
   a.ws_ml = ws.ml;
+  a.out = out;
+  a.arrivals = ws.arrivals;
+  a.min_pages = kBalancedMinPages;
+  a.unit_cost = kBalancedUnitCost;
   a.scores_stride = scores_stride;
   a.n_pool_pages = n_pool_pages;
   a.n_kv_heads = layout->n_kv_heads;
@@ -283,29 +315,37 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
   a.scale_log2 = static_cast<float>(static_cast<double>(sm_scale) * 1.4426950408889634074);
   fill_angle_tables(a, layout->t_bits);
 
-  const dim3 grid(layout->n_kv_heads, n_seqs, plan.n_chunks);
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const int group_total = n_q_heads / layout->n_kv_heads;
+  a.group_total = group_total;
+  // The role-specialised kernel shares a launch out evenly and merges in the kernel, except when
+  // the units are few and each would be shared by more work-groups than one arrival word takes
+  // well (one long sequence), or when only the partials are asked for: then one work-group per
+  // chunk, and the merge kernel.
+  const bool roles = choose_attention_kernel(layout, v_bits, n_seqs, max_seq_len) == AttentionKernel::kRoles;
+  const int n_balanced = balanced_groups(layout, n_seqs, max_seq_len);
+  const bool balanced = roles && out != nullptr && static_cast<int64_t>(n_seqs) * layout->n_kv_heads * kArriveFan >= n_balanced;
+#ifdef PQ_FORCE_GRID
+  a.grid_mode = 1;
+#else
+  a.grid_mode = balanced ? 0 : 1;
+#endif
+  const dim3 grid(layout->n_kv_heads, n_seqs, plan.n_chunks);
   hipError_t e = hipSuccess;
-  const int rt = layout->r_bits * 10 + layout->t_bits;
   // A kernel instance serves 4, 2 or 1 query heads of a KV head; larger or odd groups take
   // several passes over the cache (6 = 4 + 2, 8 = 4 + 4, ...).
-  a.group_total = group_total;
   for (int head0 = 0; head0 < group_total && e == hipSuccess;) {
     const int left = group_total - head0;
     const int G = left >= 4 ? 4 : (left >= 2 ? 2 : 1);
     a.head0 = head0;
-    if (layout->angle_quantizer == PQ_ANGLE_GROUPED) {
+    if (roles) {
+      e = a.grid_mode ? launch_attention_roles_grid(rt, G, a, q_dtype, static_cast<int>(grid.x * grid.y * grid.z), stream)
+                      : launch_attention_roles(rt, G, a, q_dtype, n_balanced, stream);
+    } else if (grouped) {
       e = v_bits == 16 ? launch_partials_ga(rt, G, a, q_dtype, grid, stream)
                        : launch_partials_ga_vq(rt, G, v_bits, a, q_dtype, grid, stream);
-      if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;
     } else if (v_bits != 16) {
       e = launch_partials_vq(rt, G, v_bits, a, q_dtype, grid, stream);
-      if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;   // quantized values: (r,t) = (4,4), (3,3) only
-    } else if (choose_attention_kernel(layout, v_bits, static_cast<int64_t>(grid.x) * grid.y * grid.z) ==
-               AttentionKernel::kRoles) {
-      e = launch_partials_roles(rt, G, a, q_dtype, grid, stream);
-      if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;
     } else {
       switch (rt) {
         case 44: e = launch_partials_g<4, 4>(G, a, q_dtype, grid, stream); break;
@@ -314,33 +354,42 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
         case 35: e = launch_partials_g<3, 5>(G, a, q_dtype, grid, stream); break;
         case 42: e = launch_partials_g<4, 2>(G, a, q_dtype, grid, stream); break;
         case 24: e = launch_partials_g<2, 4>(G, a, q_dtype, grid, stream); break;
-        default: return PQ_ERR_UNSUPPORTED;
+        default: return PQ_ERR_UNSUPPORTED;   // not reached: layout_supported() admits exactly these
       }
     }
     head0 += G;
   }
   if (e != hipSuccess) return record_hip_error(e);
+  if (out != nullptr && a.grid_mode) {
+    hipLaunchKernelGGL(pq_decode_merge_kernel, dim3(n_q_heads, n_seqs), dim3(kMergeThreads), 0, stream, ws.acc,
+                       ws.ml, seq_lens, out, n_q_heads, max_seq_len, plan.pages_per_chunk, plan.n_chunks);
+    e = hipGetLastError();
+    if (e != hipSuccess) return record_hip_error(e);
+  }
   return PQ_OK;
+}
+
+}  // namespace
+}  // namespace pq
+
+extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
+                                  int32_t n_q_heads, const void* codes_pool, const void* params_pool,
+                                  const void* v_pool, int32_t v_bits, const void* v_params_pool,
+                                  int64_t n_pool_pages, const int32_t* block_table,
+                                  int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
+                                  float sm_scale, float* scores, int64_t scores_stride,
+                                  const void* residual_keys, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
+  return decode_launch(layout, q, q_dtype, n_seqs, n_q_heads, codes_pool, params_pool, v_pool, v_bits, v_params_pool,
+                       n_pool_pages, block_table, max_pages_per_seq, seq_lens, max_seq_len, sm_scale, nullptr, scores,
+                       scores_stride, residual_keys, workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" const char* pq_decode_kernel_name(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
                                              int32_t max_seq_len, int32_t v_bits) {
   if (check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len) != PQ_OK) return "";
-  const ChunkPlan plan = plan_chunks(n_seqs, layout->n_kv_heads, max_seq_len);
-  const int64_t n_groups = static_cast<int64_t>(layout->n_kv_heads) * n_seqs * plan.n_chunks;
-  return choose_attention_kernel(layout, v_bits, n_groups) == AttentionKernel::kRoles
+  return choose_attention_kernel(layout, v_bits, n_seqs, max_seq_len) == AttentionKernel::kRoles
              ? "pq_decode_roles_kernel" : "pq_decode_partials_kernel";
-}
-
-extern "C" int pq_order_sequences(const int32_t* seq_lens, int32_t n_seqs, int32_t* order_out, void* hip_stream) {
-  if (n_seqs < 0) return PQ_ERR_INVALID_ARG;
-  if (n_seqs == 0) return PQ_OK;
-  if (!seq_lens || !order_out) return PQ_ERR_INVALID_ARG;
-  hipLaunchKernelGGL(pq_order_kernel, dim3(1), dim3(1024), 0, static_cast<hipStream_t>(hip_stream), seq_lens,
-                     n_seqs, order_out);
-  const hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return record_hip_error(e);
-  return PQ_OK;
 }
 
 extern "C" int pq_decode_merge(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
@@ -351,7 +400,7 @@ extern "C" int pq_decode_merge(const pq_layout* layout, int32_t n_seqs, int32_t 
   if (!seq_lens || !out) return PQ_ERR_INVALID_ARG;
   const ChunkPlan plan = plan_chunks(n_seqs, layout->n_kv_heads, max_seq_len);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return PQ_ERR_WORKSPACE;
-  const Workspace ws = carve_workspace(const_cast<void*>(workspace), n_seqs, n_q_heads, plan.n_chunks);
+  const Workspace ws = carve_workspace(const_cast<void*>(workspace), layout, n_seqs, n_q_heads, max_seq_len);
   if (workspace_bytes < ws.bytes) return PQ_ERR_WORKSPACE;
   hipLaunchKernelGGL(pq_decode_merge_kernel, dim3(n_q_heads, n_seqs), dim3(kMergeThreads), 0,
                      static_cast<hipStream_t>(hip_stream), ws.acc, ws.ml, seq_lens, out, n_q_heads,
@@ -367,16 +416,12 @@ extern "C" int pq_decode_attention(const pq_layout* layout, const void* q, pq_dt
                                    int64_t n_pool_pages, const int32_t* block_table,
                                    int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
                                    float sm_scale, float* out, float* scores, int64_t scores_stride,
-                                   const void* residual_keys, const int32_t* seq_order, void* workspace,
+                                   const void* residual_keys, void* workspace,
                                    size_t workspace_bytes, void* hip_stream) {
-  if (!out) return PQ_ERR_INVALID_ARG;
-  const int st = pq_decode_partials(layout, q, q_dtype, n_seqs, n_q_heads, codes_pool, params_pool, v_pool,
-                                    v_bits, v_params_pool, n_pool_pages, block_table, max_pages_per_seq, seq_lens, max_seq_len,
-                                    sm_scale, scores, scores_stride, residual_keys, seq_order, workspace,
-                                    workspace_bytes, hip_stream);
-  if (st != PQ_OK) return st;
-  return pq_decode_merge(layout, n_seqs, n_q_heads, seq_lens, max_seq_len, out, workspace, workspace_bytes,
-                         hip_stream);
+  if (!out || (reinterpret_cast<uintptr_t>(out) & 15u)) return PQ_ERR_INVALID_ARG;
+  return decode_launch(layout, q, q_dtype, n_seqs, n_q_heads, codes_pool, params_pool, v_pool, v_bits, v_params_pool,
+                       n_pool_pages, block_table, max_pages_per_seq, seq_lens, max_seq_len, sm_scale, out, scores,
+                       scores_stride, residual_keys, workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" int pq_decode_attention_static(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
@@ -385,7 +430,7 @@ extern "C" int pq_decode_attention_static(const pq_layout* layout, const void* q
                                           int64_t n_pool_pages, const int32_t* block_table,
                                           int32_t max_pages_per_seq, const int32_t* seq_lens, int32_t max_seq_len,
                                           float sm_scale, float* out, float* scores, int64_t scores_stride,
-                                          const void* residual_keys, const int32_t* seq_order, void* hip_stream) {
+                                          const void* residual_keys, void* hip_stream) {
   const int st = check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len);
   if (st != PQ_OK) return st;
   const size_t need = pq_decode_workspace_bytes(layout, n_seqs, n_q_heads, max_seq_len);
@@ -395,7 +440,7 @@ extern "C" int pq_decode_attention_static(const pq_layout* layout, const void* q
   if (sp != PQ_OK) return sp;
   return pq_decode_attention(layout, q, q_dtype, n_seqs, n_q_heads, codes_pool, params_pool, v_pool, v_bits,
                              v_params_pool, n_pool_pages, block_table, max_pages_per_seq, seq_lens, max_seq_len,
-                             sm_scale, out, scores, scores_stride, residual_keys, seq_order, ws, need, hip_stream);
+                             sm_scale, out, scores, scores_stride, residual_keys, ws, need, hip_stream);
 }
 
 extern "C" int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,

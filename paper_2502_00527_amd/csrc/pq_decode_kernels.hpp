@@ -55,11 +55,16 @@ struct DecodeArgs {
   const __half* residual;   // [seq][kv_head][g][d] un-quantized keys of the last, incomplete group (or null)
   const int32_t* block_table;
   const int32_t* seq_lens;
-  const int32_t* seq_order;  // optional: sequence handled by grid row y (null: y itself)
   int32_t n_seqs;
   float* scores;
-  float* ws_acc;            // [seq][q_head][chunk][128]
-  float* ws_ml;             // [seq][q_head][chunk][2] = (m in log2 units, l)
+  float* ws_acc;            // [seq][q_head][chunk][128]; balanced launches: [slot][head of the group][128]
+  float* ws_ml;             // [seq][q_head][chunk][2] = (m in log2 units, l); balanced: [slot][head of the group][2]
+  // launches whose work-groups share the pages out evenly and merge in the kernel (pq_decode_sched.hpp)
+  float* out;               // [seq][q_head][128]
+  uint64_t* arrivals;       // one arrival word per (sequence, KV head), then one per segment slot
+  int32_t min_pages;        // smallest share of a work-group, in pages
+  int32_t unit_cost;        // what starting on a (sequence, KV head) costs a work-group, in pages
+  int32_t grid_mode;        // role-specialised kernel: one work-group per (KV head, sequence, chunk) instead
   int64_t scores_stride;
   int64_t n_pool_pages;
   int32_t n_kv_heads;
@@ -162,8 +167,10 @@ __device__ __forceinline__ void wave_lds_sync() {
 // loads are non-temporal.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kAuxStream = 2;     // gfx950 cache-policy bit "nt"
 constexpr int kAuxCached = 0;
+constexpr int kAuxDevice = 16;    // gfx950 cache-policy bit "sc1": performed past the per-XCD L2s, coherent device-wide
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
   // raw buffer, 32-bit data format, no swizzle
@@ -398,6 +405,108 @@ __device__ __forceinline__ void consume_quantized(const uint4& u, int tok0, uint
   }
 }
 
+// ---- pieces shared by the attention kernels and the score-only kernel -------------------
+
+// q[dim][head] as fp32 in LDS (heads beyond G zero), and the grid's (cos, sin) pairs: first step of
+// the table build; also read by the residual-key dot products and by the per-group table builds
+// of the grouped angle quantizer.  In two halves, so that a kernel can put other loads between
+// the fetch and its use; a work-group barrier must follow the store before LDS is read.
+template <int G>
+struct QueryRegs {
+  float q[G];
+  float2 cs;
+};
+template <int G, typename QT>
+__device__ __forceinline__ QueryRegs<G> fetch_query(const QT* qb, const DecodeArgs& a, int tid) {
+  QueryRegs<G> r = {};
+  if (tid < kHeadDim) {
+#pragma unroll
+    for (int h = 0; h < G; ++h) r.q[h] = static_cast<float>(qb[h * kHeadDim + tid]);
+  } else if (tid < kHeadDim + kMaxAngleBins) {
+    r.cs = make_float2(a.cos_tab[tid - kHeadDim], a.sin_tab[tid - kHeadDim]);
+  }
+  return r;
+}
+template <int G>
+__device__ __forceinline__ void store_query_lds(float (*q_lds)[4], float2* trig, const QueryRegs<G>& r, int tid) {
+  if (tid < kHeadDim) {
+#pragma unroll
+    for (int h = 0; h < 4; ++h) q_lds[tid][h] = h < G ? r.q[h < G ? h : 0] : 0.f;
+  } else if (tid < kHeadDim + kMaxAngleBins) {
+    trig[tid - kHeadDim] = r.cs;
+  }
+}
+template <int G, typename QT>
+__device__ __forceinline__ void load_query_lds(float (*q_lds)[4], float2* trig, const QT* qb, const DecodeArgs& a,
+                                               int tid) {
+  store_query_lds<G>(q_lds, trig, fetch_query<G, QT>(qb, a, tid), tid);
+}
+
+// Table of the uniform angle grid (Section 3.3): T[j][a][h] = q_x[h][j] cos(theta~_a) + q_y[h][j]
+// sin(theta~_a), 16 bytes per (pair, state) entry whatever G is, from the q and (cos, sin) that
+// load_query_lds left in LDS; written by all `n_threads` threads of the work-group.
+template <int TB>
+__device__ __forceinline__ void build_uniform_table(uint8_t* lut, const float (*q_lds)[4], const float2* trig, int tid,
+                                                    int n_threads) {
+  constexpr int NA = 1 << TB;
+  const uint32_t lut_a = lds_addr(lut), q_a = lds_addr(q_lds), t_a = lds_addr(trig);
+  for (int idx = tid; idx < kPairs * NA; idx += n_threads) {
+    const int j = idx >> TB, s = idx & (NA - 1);
+    const f32x2 cs = *(const PQ_LDS f32x2*)static_cast<uintptr_t>(t_a + s * 8);
+    const f32x4 qx = *(const PQ_LDS f32x4*)static_cast<uintptr_t>(q_a + j * 16);
+    const f32x4 qy = *(const PQ_LDS f32x4*)static_cast<uintptr_t>(q_a + (j + kPairs) * 16);
+    f32x4 t;
+    t.x = fmaf(qx.x, cs.x, qy.x * cs.y);
+    t.y = fmaf(qx.y, cs.x, qy.y * cs.y);
+    t.z = fmaf(qx.z, cs.x, qy.z * cs.y);
+    t.w = fmaf(qx.w, cs.x, qy.w * cs.y);
+    *(PQ_LDS f32x4*)static_cast<uintptr_t>(lut_a + idx * 16) = t;
+  }
+}
+
+// Radius parameters of this lane's 16 pairs from the four 128-bit words {fp16 s, fp16 z} x 4:
+// rho~ = c * sf + zz with zz = z + s / 2 (mid-point reconstruction, Section 3.2).
+__device__ __forceinline__ void unpack_radius_params(const uint4 (&praw)[4], float (&sf)[16], float (&zz)[16]) {
+#pragma unroll
+  for (int v4 = 0; v4 < 4; ++v4) {
+    const uint32_t w4[4] = {praw[v4].x, praw[v4].y, praw[v4].z, praw[v4].w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const __half2 sz = *reinterpret_cast<const __half2*>(&w4[e]);
+      const float s = __low2float(sz), z = __high2float(sz);
+      sf[v4 * 4 + e] = s;
+      zz[v4 * 4 + e] = fmaf(0.5f, s, z);
+    }
+  }
+}
+
+// Raw scores of a residual group (the un-quantized fp16 keys of a sequence's last, incomplete
+// group): plain dot products in the score-phase lane layout (lane = (pair block row, token col),
+// each lane takes the 32 dims of its 16 pairs), folded like the table-lookup partial sums.  Key
+// rows past `nv_res` read as zero.  `emit(pass, score)` is called once per pass of 16 tokens with
+// the score of token 16 * pass + col for the lane's head (valid in the lanes that own a head).
+template <int G, typename Emit>
+__device__ __forceinline__ void residual_scores(const __half* res_rows, int nv_res, uint32_t q_lds_addr, int row,
+                                                int col, Emit emit) {
+  const __amdgpu_buffer_rsrc_t rs_res = make_rsrc(res_rows, static_cast<uint32_t>(nv_res) * (kHeadDim * 2));
+  const uint32_t voff_res = col * (kHeadDim * 2) + row * 32;
+  const uint32_t qs_row = q_lds_addr + row * (16 * 16);
+#pragma unroll 1
+  for (int s = 0; s < 8; ++s) {
+    uint4 kx[2], ky[2];
+    const uint32_t soff = s * 16 * kHeadDim * 2;
+    kx[0] = buf_load16<kAuxCached>(rs_res, voff_res, soff);
+    kx[1] = buf_load16<kAuxCached>(rs_res, voff_res + 16, soff);
+    ky[0] = buf_load16<kAuxCached>(rs_res, voff_res + kPairs * 2, soff);
+    ky[1] = buf_load16<kAuxCached>(rs_res, voff_res + kPairs * 2 + 16, soff);
+    float part[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) part[h] = 0.f;
+    dense_steps<G>(kx, ky, qs_row, part);
+    emit(s, fold_rows<G>(part));
+  }
+}
+
 // Grouped angle quantizer: this wavefront's table T[j][a][h] = q_x[h][j] cos(theta~) + q_y[h][j]
 // sin(theta~), theta~ = (a + 1/2) s_t[j] + z_t[j] (Section 3.2 reconstruction, Section 3.3 table),
 // for the page whose angle parameters {fp16 s_t, fp16 z_t} of pair `lane` are in `tpar`.
@@ -444,16 +553,15 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   __shared__ __attribute__((aligned(16))) float red_own[GA ? 4 : kWaves * G * kHeadDim];
   static_assert(!GA || kLutBytes >= G * kHeadDim * 4, "table space too small for the accumulators");
   __shared__ float red_ml[kWaves][G][3];                              // m, l, sum of p * zero-point
-  __shared__ __attribute__((aligned(16))) float q_lds[kHeadDim][4];   // q[dim][head] for residual keys
+  __shared__ __attribute__((aligned(16))) float q_lds[kHeadDim][4];   // q[dim][head]: table build, residual keys
+  __shared__ float2 trig[kMaxAngleBins];                              // (cos, sin) of the uniform grid's bin centres
   __shared__ float res_sc[kGroup * G];                                // raw scores of the residual group
 
   // Chunk-major launch order: the KV heads of one page are neighbours in memory and run
   // together; every sequence's first chunks run first, and the chunks that only long sequences
   // have (with the empty work-groups of the short ones) come last, which balances ragged batches.
   const int kvh = blockIdx.x, chunk = blockIdx.z;
-  // Work-groups start in grid order; a caller-given order lets long sequences start first.
-  const int seq = a.seq_order ? a.seq_order[blockIdx.y] : static_cast<int>(blockIdx.y);
-  if (seq < 0 || seq >= a.n_seqs) return;
+  const int seq = blockIdx.y;
   const int L = min(a.seq_lens[seq], a.max_seq_len);
   if (L <= 0) return;
   const int n_pages = (L + kGroup - 1) / kGroup;
@@ -579,22 +687,10 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   // (built while the first page's loads, issued above, are in flight)
   {
     const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim;
+    load_query_lds<G, QT>(q_lds, trig, qb, a, tid);
     if constexpr (!GA) {
-      float* lf = reinterpret_cast<float*>(lut);
-      for (int idx = tid; idx < kPairs * NA; idx += kThreads) {
-        const int j = idx >> TB, s = idx & (NA - 1);
-        const float cs = a.cos_tab[s], sn = a.sin_tab[s];
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-          const float qx = static_cast<float>(qb[h * kHeadDim + j]);
-          const float qy = static_cast<float>(qb[h * kHeadDim + j + kPairs]);
-          lf[idx * 4 + h] = fmaf(qx, cs, qy * sn);
-        }
-      }
-    }
-    if (tid < kHeadDim) {
-#pragma unroll
-      for (int h = 0; h < 4; ++h) q_lds[tid][h] = h < G ? static_cast<float>(qb[h * kHeadDim + tid]) : 0.f;
+      __syncthreads();
+      build_uniform_table<TB>(lut, q_lds, trig, tid, kThreads);
     }
   }
   __syncthreads();
@@ -604,27 +700,10 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   // layout (each lane takes the 32 dims of its 16 pairs) and with the same fold; key rows past
   // the sequence end read as zero.  The loop below picks the scores up from LDS.
   if (res_page >= page0 + wave && res_page < page0 + npg && ((res_page - page0 - wave) & (kWaves - 1)) == 0) {
-    const int nv_res = L - res_page * kGroup;
-    const __amdgpu_buffer_rsrc_t rs_res = make_rsrc(
-        a.residual + (static_cast<int64_t>(seq) * a.n_kv_heads + kvh) * (kGroup * kHeadDim),
-        static_cast<uint32_t>(nv_res) * (kHeadDim * 2));
-    const uint32_t voff_res = col * (kHeadDim * 2) + row * 32;
-    const uint32_t qs_row = lds_addr(q_lds) + row * (16 * 16);
-#pragma unroll 1
-    for (int s = 0; s < 8; ++s) {
-      uint4 kx[2], ky[2];
-      const uint32_t soff = s * 16 * kHeadDim * 2;
-      kx[0] = buf_load16<kAuxCached>(rs_res, voff_res, soff);
-      kx[1] = buf_load16<kAuxCached>(rs_res, voff_res + 16, soff);
-      ky[0] = buf_load16<kAuxCached>(rs_res, voff_res + kPairs * 2, soff);
-      ky[1] = buf_load16<kAuxCached>(rs_res, voff_res + kPairs * 2 + 16, soff);
-      float part[G];
-#pragma unroll
-      for (int h = 0; h < G; ++h) part[h] = 0.f;
-      dense_steps<G>(kx, ky, qs_row, part);
-      const float v = fold_rows<G>(part);
-      if (owner) res_sc[(s * 16 + col) * G + my_head] = v;
-    }
+    residual_scores<G>(a.residual + (static_cast<int64_t>(seq) * a.n_kv_heads + kvh) * (kGroup * kHeadDim),
+                       L - res_page * kGroup, lds_addr(q_lds), row, col, [&](int s, float v) {
+                         if (owner) res_sc[(s * 16 + col) * G + my_head] = v;
+                       });
     wave_lds_sync();
   }
 
@@ -646,17 +725,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
 
     // radius parameters of this lane's 16 pairs: rho~ = c * s + (z + s/2)
     float sf[16], zz[16];
-#pragma unroll
-    for (int v4 = 0; v4 < 4; ++v4) {
-      const uint32_t w4[4] = {praw[v4].x, praw[v4].y, praw[v4].z, praw[v4].w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const __half2 sz = *reinterpret_cast<const __half2*>(&w4[e]);
-        const float s = __low2float(sz), z = __high2float(sz);
-        sf[v4 * 4 + e] = s;
-        zz[v4 * 4 + e] = fmaf(0.5f, s, z);
-      }
-    }
+    unpack_radius_params(praw, sf, zz);
 
     // ---- scores of the page's 128 tokens: 8 passes of 16 tokens ----
     float sc[8];
@@ -819,7 +888,8 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
   constexpr int kLutBytes = kPairs * ROW;
   constexpr int kParamSets = GA ? 2 : 1;
   __shared__ __attribute__((aligned(16))) uint8_t lut[(GA ? kWaves : 1) * kLutBytes];   // GA: one table per wavefront
-  __shared__ __attribute__((aligned(16))) float q_lds[kHeadDim][4];   // q[dim][head]: table rebuilds, residual keys
+  __shared__ __attribute__((aligned(16))) float q_lds[kHeadDim][4];   // q[dim][head]: table builds, residual keys
+  __shared__ float2 trig[kMaxAngleBins];                              // (cos, sin) of the uniform grid's bin centres
 
   const int kvh = blockIdx.x, seq = blockIdx.y, chunk = blockIdx.z;
   const int L = min(a.seq_lens[seq], a.max_seq_len);
@@ -872,22 +942,10 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
   }
   {
     const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim;
-    if (tid < kHeadDim) {
-#pragma unroll
-      for (int h = 0; h < 4; ++h) q_lds[tid][h] = h < G ? static_cast<float>(qb[h * kHeadDim + tid]) : 0.f;
-    }
+    load_query_lds<G, QT>(q_lds, trig, qb, a, tid);
     if constexpr (!GA) {
-      float* lf = reinterpret_cast<float*>(lut);
-      for (int idx = tid; idx < kPairs * NA; idx += kThreads) {
-        const int j = idx >> TB, s = idx & (NA - 1);
-        const float cs = a.cos_tab[s], sn = a.sin_tab[s];
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-          const float qx = static_cast<float>(qb[h * kHeadDim + j]);
-          const float qy = static_cast<float>(qb[h * kHeadDim + j + kPairs]);
-          lf[idx * 4 + h] = fmaf(qx, cs, qy * sn);
-        }
-      }
+      __syncthreads();
+      build_uniform_table<TB>(lut, q_lds, trig, tid, kThreads);
     }
   }
   __syncthreads();
@@ -898,27 +956,11 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
   // products, by the wavefront that owns the group's page (same lane layout and fold as below).
   if (res_page >= page0 + wave && res_page < page0 + npg && ((res_page - page0 - wave) & (kWaves - 1)) == 0) {
     const int nv_res = L - res_page * kGroup;
-    const __amdgpu_buffer_rsrc_t rs_res = make_rsrc(
-        a.residual + (static_cast<int64_t>(seq) * a.n_kv_heads + kvh) * (kGroup * kHeadDim),
-        static_cast<uint32_t>(nv_res) * (kHeadDim * 2));
-    const uint32_t voff_res = col * (kHeadDim * 2) + row * 32;
-    const uint32_t qs_row = lds_addr(q_lds) + row * (16 * 16);
-#pragma unroll 1
-    for (int s = 0; s < 8; ++s) {
-      uint4 kx[2], ky[2];
-      const uint32_t soff = s * 16 * kHeadDim * 2;
-      kx[0] = buf_load16<kAuxCached>(rs_res, voff_res, soff);
-      kx[1] = buf_load16<kAuxCached>(rs_res, voff_res + 16, soff);
-      ky[0] = buf_load16<kAuxCached>(rs_res, voff_res + kPairs * 2, soff);
-      ky[1] = buf_load16<kAuxCached>(rs_res, voff_res + kPairs * 2 + 16, soff);
-      float part[G];
-#pragma unroll
-      for (int h = 0; h < G; ++h) part[h] = 0.f;
-      dense_steps<G>(kx, ky, qs_row, part);
-      const float v = fold_rows<G>(part);
-      const int tok = s * 16 + col;
-      if (owner && tok < nv_res) out_row[static_cast<int64_t>(res_page) * kGroup + tok] = v;
-    }
+    residual_scores<G>(a.residual + (static_cast<int64_t>(seq) * a.n_kv_heads + kvh) * (kGroup * kHeadDim), nv_res,
+                       lds_addr(q_lds), row, col, [&](int s, float v) {
+                         const int tok = s * 16 + col;
+                         if (owner && tok < nv_res) out_row[static_cast<int64_t>(res_page) * kGroup + tok] = v;
+                       });
   }
 
   for (int i = 0; i < n_w; ++i) {
@@ -935,17 +977,7 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
       wave_lds_sync();
     }
     float sf[16], zz[16];
-#pragma unroll
-    for (int v4 = 0; v4 < 4; ++v4) {
-      const uint32_t w4[4] = {praw[v4].x, praw[v4].y, praw[v4].z, praw[v4].w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const __half2 sz = *reinterpret_cast<const __half2*>(&w4[e]);
-        const float s = __low2float(sz), z = __high2float(sz);
-        sf[v4 * 4 + e] = s;
-        zz[v4 * 4 + e] = fmaf(0.5f, s, z);
-      }
-    }
+    unpack_radius_params(praw, sf, zz);
 #pragma unroll
     for (int v4 = 0; v4 < 4; ++v4) praw[v4] = buf_load16<kAuxCached>(rp_nxt, voff_params, v4 * 16);
     if constexpr (GA) tpar = buf_load4<kAuxCached>(rp_nxt, lane * 4, kPairs * 4);
@@ -956,15 +988,7 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
       for (int h = 0; h < G; ++h) part[h] = 0.f;
       score_steps<G, RB, TB, 0>(cu[s], lut_row0, sf, zz, part);
       cu[s] = load_unit<W>(rc_nxt, voff_codes, s * 16 * UB);       // next page's pass s
-      float sc;
-      if constexpr (G == 4) {
-        sc = tsum16(tsum32(part[0], part[2]), tsum32(part[1], part[3]));
-      } else if constexpr (G == 2) {
-        const float b = tsum32(part[0], part[1]);
-        sc = tsum16(b, b);
-      } else {
-        sc = sum_rows(part[0]);
-      }
+      const float sc = fold_rows<G>(part);
       const int tok = s * 16 + col;
       if (owner && tok < nv_cur && pi != res_page) out_row[static_cast<int64_t>(pi) * kGroup + tok] = sc;
     }

@@ -1,23 +1,36 @@
-// Instantiations of the role-specialised attention kernel (fp16 values, uniform angle grid).
+// Instantiations of the role-specialised attention kernel (fp16 values, uniform angle grid): the
+// kernels that share a launch out evenly and merge inside.  pq_decode_roles_grid.hip compiles this
+// file a second time for the one-work-group-per-chunk kernels.
 #include "pq_decode_roles.hpp"
+
+#ifndef PQ_ROLES_BALANCED
+#define PQ_ROLES_BALANCED true
+#define PQ_ROLES_LAUNCH launch_attention_roles
+#endif
 
 namespace pq {
 namespace {
 
+template <int G, int RB, int TB, typename QT, bool SCORES>
+void launch_mode(const DecodeArgs& a, const dim3 grid, hipStream_t st) {
+  hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, QT, SCORES, PQ_ROLES_BALANCED>), grid, dim3(kRoleThreads), 0, st, a);
+}
+
 template <int G, int RB, int TB>
-void launch_one(const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st) {
+void launch_one(const DecodeArgs& a, pq_dtype qdt, int n_wg, hipStream_t st) {
+  const dim3 grid(n_wg);
   const bool sc = a.scores != nullptr;
   if (qdt == PQ_F16) {
-    if (sc) hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, __half, true>), grid, dim3(kRoleThreads), 0, st, a);
-    else    hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, __half, false>), grid, dim3(kRoleThreads), 0, st, a);
+    if (sc) launch_mode<G, RB, TB, __half, true>(a, grid, st);
+    else    launch_mode<G, RB, TB, __half, false>(a, grid, st);
   } else {
-    if (sc) hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, float, true>), grid, dim3(kRoleThreads), 0, st, a);
-    else    hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, float, false>), grid, dim3(kRoleThreads), 0, st, a);
+    if (sc) launch_mode<G, RB, TB, float, true>(a, grid, st);
+    else    launch_mode<G, RB, TB, float, false>(a, grid, st);
   }
 }
 
 template <int RB, int TB>
-bool launch_g(int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st) {
+bool launch_g(int G, const DecodeArgs& a, pq_dtype qdt, int grid, hipStream_t st) {
   switch (G) {
     case 1: launch_one<1, RB, TB>(a, qdt, grid, st); return true;
     case 2: launch_one<2, RB, TB>(a, qdt, grid, st); return true;
@@ -28,7 +41,7 @@ bool launch_g(int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t s
 
 }  // namespace
 
-hipError_t launch_partials_roles(int rt, int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st) {
+hipError_t PQ_ROLES_LAUNCH(int rt, int G, const DecodeArgs& a, pq_dtype qdt, int grid, hipStream_t st) {
   bool ok = false;
   switch (rt) {
     case 44: ok = launch_g<4, 4>(G, a, qdt, grid, st); break;
@@ -44,3 +57,4 @@ hipError_t launch_partials_roles(int rt, int G, const DecodeArgs& a, pq_dtype qd
 }
 
 }  // namespace pq
+

@@ -59,12 +59,14 @@ def test_page_sizes_and_bit_accounting(lib):
 
 def test_workspace_size_follows_the_chunk_plan(lib):
     lay = pq.Layout(128, 4, 4, 128, 8)
-    # 16 seqs x 8 kv heads, 256 pages: chunks of 32 pages -> 8 chunks per sequence
+    # 16 seqs x 8 kv heads, 256 pages: chunks of 32 pages -> 8 chunks per sequence (grid launches);
+    # balanced launches need (768 work-groups + 128 units) x 4 heads slots, which is fewer; plus
+    # 8-byte arrival words: one per unit and one per segment slot
     n = pq.pq_decode_workspace_bytes(lay, 16, 32, 32768)
-    assert n == 16 * 32 * 8 * 128 * 4 + 16 * 32 * 8 * 2 * 4
-    # one sequence x 8 kv heads, 1024 pages: chunks shrink to 16 pages so that 512 work-groups exist
+    assert n == 16 * 32 * 8 * 128 * 4 + 16 * 32 * 8 * 2 * 4 + (128 + 768 + 128) * 8
+    # one sequence x 8 kv heads, 1024 pages: (768 + 8) x 4 balanced slots exceed the 32 x 64 chunk slots
     n = pq.pq_decode_workspace_bytes(pq.Layout(128, 3, 3, 128, 8), 1, 32, 131072)
-    assert n == 32 * 64 * 128 * 4 + 32 * 64 * 2 * 4
+    assert n == 776 * 4 * 128 * 4 + 776 * 4 * 2 * 4 + (8 + 768 + 8) * 8 + 128      # rounded up to 256
     assert pq.pq_decode_workspace_bytes(lay, 1, 32, 1) > 0
     assert pq.pq_decode_workspace_bytes(lay, 0, 32, 128) == 0
     assert pq.pq_decode_workspace_bytes(lay, 1, 12, 128) == 0      # 12 query heads over 8 kv heads
@@ -84,22 +86,22 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     bad = pq.Layout(128, 7, 1, 128, 8)
     assert lib.pq_encode_keys(ctypes.byref(bad), null, 0, 1024, 128, 10, null, null, null, 4, null) == -2
     st = lib.pq_decode_attention(ctypes.byref(lay), null, 0, 1, 32, null, null, null, 16, null, 4, null, 1, null, 128,
-                                 0.1, null, null, 0, null, null, null, 0, null)
+                                 0.1, null, null, 0, null, null, 0, null)
     assert st == -1
     fake = ctypes.c_void_p(4096)
     st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 16, null, 4, fake, 1, fake, 128,
-                                0.1, null, 0, null, null, null, 0, null)
+                                0.1, null, 0, null, null, 0, null)
     assert st == -3 and "workspace" in pq.pq_strerror(st)
     # more pages needed than the block table is wide
     st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 16, null, 4, fake, 1, fake, 129,
-                                0.1, null, 0, null, null, fake, 1 << 20, null)
+                                0.1, null, 0, null, fake, 1 << 20, null)
     assert st == -1
     # quantized values need their parameter pool; 3-bit values are not built
     st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 4, null, 4, fake, 1, fake, 128,
-                                0.1, null, 0, null, null, fake, 1 << 20, null)
+                                0.1, null, 0, null, fake, 1 << 20, null)
     assert st == -1
     st = lib.pq_decode_partials(ctypes.byref(lay), fake, 0, 1, 32, fake, fake, fake, 3, fake, 4, fake, 1, fake, 128,
-                                0.1, null, 0, null, null, fake, 1 << 20, null)
+                                0.1, null, 0, null, fake, 1 << 20, null)
     assert st == -2
     assert pq.pq_vq_bytes_per_page(lay, 4) == 8 * 128 * 64 and pq.pq_vq_bytes_per_page(lay, 2) == 8 * 128 * 32
     assert pq.pq_vq_bytes_per_page(lay, 3) == 0 and pq.pq_vq_params_bytes_per_page(lay) == 8 * 128 * 4
@@ -110,13 +112,12 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     # grouped angles exist for (4,4) and (3,3) only
     grouped = pq.Layout(128, 5, 3, 128, 8, 1)
     st = lib.pq_decode_partials(ctypes.byref(grouped), fake, 0, 1, 32, fake, fake, fake, 16, null, 4, fake, 1, fake, 128,
-                                0.1, null, 0, null, null, fake, 1 << 20, null)
+                                0.1, null, 0, null, fake, 1 << 20, null)
     assert st == -2
     # the allocation-free variant refuses, on the host, shapes beyond its static scratch array
     st = lib.pq_decode_attention_static(ctypes.byref(lay), fake, 0, 512, 32, fake, fake, fake, 16, null, 4, fake, 128,
-                                        fake, 16384, 0.1, fake, null, 0, null, null, null)
+                                        fake, 16384, 0.1, fake, null, 0, null, null)
     assert st == -5 and "static" in pq.pq_strerror(st)
-    assert lib.pq_order_sequences(null, 5, null, null) == -1 and lib.pq_order_sequences(null, 0, null, null) == 0
     assert pq.pq_version() >= 102
 
 

@@ -458,46 +458,6 @@ def test_two_streams_with_their_own_workspaces():
         assert torch.equal(out_a, ref_a) and torch.equal(out_b, ref_b)
 
 
-def test_sequence_order_hint():
-    """pq_order_sequences sorts by decreasing length (ties by index); a decode call given that
-    order, or any other permutation, returns exactly what it returns without one; entries outside
-    the batch are skipped without harm."""
-    from paper_2502_00527_amd import pq_order_sequences
-    from paper_2502_00527_amd.cache import build_device_cache
-
-    wl = WL["ragged"].scaled(n_seqs=37, n_q_heads=8, n_kv_heads=2, max_len=3000, min_len=1)
-    lens = W.seq_lengths(wl)
-    lens[5] = lens[9] = lens[20]          # ties
-    lens[11] = 0
-    cache = build_device_cache(wl, lens=lens)
-    plain = cache.decode().clone()
-    order = torch.full((wl.n_seqs,), -7, dtype=torch.int32, device="cuda:0")
-    pq_order_sequences(cache.seq_lens, order)
-    torch.cuda.synchronize()
-    want = sorted(range(wl.n_seqs), key=lambda i: (-int(lens[i]), i))
-    assert order.cpu().tolist() == want
-    cache.seq_order = order
-    assert torch.equal(cache.decode(), plain)
-    cache.seq_order = torch.flip(order, dims=[0]).contiguous()
-    assert torch.equal(cache.decode(), plain)
-    # an order with entries outside the batch: those rows keep what the buffer held
-    bad = order.clone()
-    bad[0] = wl.n_seqs + 3
-    bad[1] = -1
-    cache.seq_order = bad
-    out = torch.full_like(plain, 123.0)
-    cache.decode(out)
-    torch.cuda.synchronize()
-    skipped = [want[0], want[1]]
-    keep = [i for i in range(wl.n_seqs) if i not in skipped]
-    assert torch.equal(out[keep], plain[keep])
-    # more sequences than the sorter handles: identity
-    many = torch.randint(1, 500, (3000,), dtype=torch.int32, device="cuda:0")
-    ident = torch.empty(3000, dtype=torch.int32, device="cuda:0")
-    pq_order_sequences(many, ident)
-    assert ident.cpu().tolist() == list(range(3000))
-
-
 def test_random_shapes():
     """Seeded sweep over shapes the fixed cases do not name: random batch sizes, query-group
     sizes, bit allocations, angle quantizers and ragged lengths (lengths of 0 included)."""

@@ -30,7 +30,7 @@ def _raw_static_call(lib, cache, out, scores=None):
         wl.n_seqs, wl.n_q_heads, cache.codes.data_ptr(), cache.params.data_ptr(), cache.values.data_ptr(), 16, null,
         cache.n_pool_pages, cache.block_table.data_ptr(), cache.block_table.shape[1], cache.seq_lens.data_ptr(),
         cache.max_seq_len, ctypes.c_float(cache.sm_scale), out.data_ptr(),
-        null if scores is None else scores.data_ptr(), 0 if scores is None else scores.shape[-1], null, null,
+        null if scores is None else scores.data_ptr(), 0 if scores is None else scores.shape[-1], null,
         ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
     return st
 
@@ -79,5 +79,5 @@ def test_static_scratch_rejects_shapes_beyond_its_size():
     fake = ctypes.c_void_p(4096)
     null = ctypes.c_void_p(0)
     st = lib.pq_decode_attention_static(ctypes.byref(lay), fake, 0, 512, 32, fake, fake, fake, 16, null, 4, fake, 128, fake,
-                                        16384, ctypes.c_float(0.1), fake, null, 0, null, null, null)
+                                        16384, ctypes.c_float(0.1), fake, null, 0, null, null)
     assert st == -5 and "static" in pq.pq_strerror(st)
