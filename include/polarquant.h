@@ -49,8 +49,12 @@
  * s = (max - min) / (2^b - 1) over the d values of one token of one head (round half to even;
  * s, z stored as fp16 and used as stored); dequantized value = code * s + z.
  *   vq pool     : [page][kv_head][token block = token / T][dim slice = dim / 8][unit 16 bytes],
- *                 T = 16 / b tokens per unit; token i of the unit is the 8*b-bit field i of the
- *                 unit, dim k of that token the b-bit field k of it (little-endian)
+ *                 T = 16 / b tokens per unit.  A unit is four 32-bit words; a word holds the codes of
+ *                 two consecutive tokens, the even one in its low 16 bits and the odd one in its high
+ *                 16 bits, the same dims in both halves, dim after dim from bit 0 up.  b = 4: a half
+ *                 holds 4 dims, word j = 2 * (token pair) + (0: dims 0-3 of the slice, 1: dims 4-7);
+ *                 b = 2: a half holds the slice's 8 dims, word j = token pair.  (Two tokens per word so
+ *                 that one mask yields the fp16 pair a two-term dot-product instruction takes.)
  *   vq params   : [page][kv_head][token g]{fp16 s, fp16 z}
  *
  * Optional grouped angle quantizer (pq_layout.angle_quantizer = PQ_ANGLE_GROUPED): the angle

@@ -110,11 +110,37 @@ def params_bytes_per_page(n_kv_heads: int, head_dim: int, grouped_angles: bool =
     return n_kv_heads * (head_dim // 2) * 2 * 2 * (2 if grouped_angles else 1)
 
 
+def _value_unit_order(bits: int):
+    """How the T x 8 codes of a unit (T = 16 / bits tokens, 8 dims) are laid into its four 32-bit words.
+
+    A word holds the codes of two consecutive tokens: the even token in the low 16 bits, the odd
+    token in the high 16 bits, the same dims in both halves, dims in increasing order from bit 0.
+    4-bit codes: a half holds 4 dims, so word j = 2 * (token pair) + (dim half: dims 0-3 / 4-7).
+    2-bit codes: a half holds all 8 dims, so word j = token pair.
+    Returns (token index, dim index) arrays of the 128 / bits fields in storage order (field 0 at
+    bit 0 of word 0).
+    """
+    T = 16 // bits
+    per_half = 16 // bits                       # fields in a 16-bit half
+    tok, dim = [], []
+    for word in range(4):
+        if bits == 4:
+            pair, dims0 = word // 2, 4 * (word % 2)
+        else:
+            pair, dims0 = word, 0
+        for half in range(2):
+            for f in range(per_half):
+                tok.append(2 * pair + half)
+                dim.append(dims0 + f)
+    assert sorted(zip(tok, dim)) == [(t, k) for t in range(T) for k in range(8)]
+    return np.array(tok), np.array(dim)
+
+
 def pack_value_page_stream(codes: np.ndarray, bits: int, group_tokens: int) -> np.ndarray:
     """Quantized value codes of one sequence -> pages.
 
     codes int [L, H, d] (b-bit each) -> uint8 [n_pages, H, g / T, d / 8, 16], T = 16 / bits tokens
-    per unit; slots past the sequence end are zero.
+    per unit (see _value_unit_order for the inside of a unit); slots past the sequence end are zero.
     """
     L, H, d = codes.shape
     g = group_tokens
@@ -126,8 +152,10 @@ def pack_value_page_stream(codes: np.ndarray, bits: int, group_tokens: int) -> n
     # [page, token block, token in unit, H, dim slice, dim in slice]
     x = full.reshape(n_pages, g // T, T, H, d // 8, 8)
     x = x.transpose(0, 3, 1, 4, 2, 5)                                       # [page, H, block, slice, T, 8]
-    bit_planes = ((x[..., None] >> np.arange(bits)) & 1).astype(np.uint8)     # LSB first per element
-    stream = bit_planes.reshape(n_pages, H, g // T, d // 8, T * 8 * bits)     # token-major, dim, bit
+    tok, dim = _value_unit_order(bits)
+    fields = x[..., tok, dim]                                               # storage order
+    bit_planes = ((fields[..., None] >> np.arange(bits)) & 1).astype(np.uint8)   # LSB first per field
+    stream = bit_planes.reshape(n_pages, H, g // T, d // 8, T * 8 * bits)
     return np.packbits(stream, axis=-1, bitorder="little")
 
 
@@ -135,7 +163,10 @@ def unpack_value_pages(pages: np.ndarray, length: int, bits: int) -> np.ndarray:
     """Inverse of pack_value_page_stream: uint8 [n_pages, H, g/T, d/8, 16] -> int64 [length, H, d]."""
     n_pages, H, n_blocks, n_slices, _ = pages.shape
     T = 16 // bits
-    b = np.unpackbits(pages, axis=-1, bitorder="little").reshape(n_pages, H, n_blocks, n_slices, T, 8, bits)
-    x = (b.astype(np.int64) << np.arange(bits)).sum(axis=-1)                # [page, H, block, slice, T, 8]
+    b = np.unpackbits(pages, axis=-1, bitorder="little").reshape(n_pages, H, n_blocks, n_slices, T * 8, bits)
+    fields = (b.astype(np.int64) << np.arange(bits)).sum(axis=-1)           # storage order
+    tok, dim = _value_unit_order(bits)
+    x = np.zeros((n_pages, H, n_blocks, n_slices, T, 8), np.int64)
+    x[..., tok, dim] = fields
     x = x.transpose(0, 2, 4, 1, 3, 5).reshape(n_pages * n_blocks * T, H, n_slices * 8)
     return x[:length]

@@ -361,46 +361,88 @@ __device__ __forceinline__ void consume_values(const uint4 (&vv)[4], int it0, ui
   }
 }
 
-// Quantized values (token-wise b-bit codes, paper Section 2): one 16-byte unit holds T = 16 / b
-// tokens x this lane's 8 dims.  acc[h][k] += (p_h[token] * s_token) * code[token][k]; the
-// probabilities in LDS are already multiplied by the token's scale, the zero-points are summed
-// separately (sum_n p_n z_n is the same for every dim).  `tok0` is the unit's first token.
+// ---- quantized values (token-wise b-bit codes, paper Section 2) ----------------------------
+// acc[h][k] += sum over the unit's tokens of (p_h[token] * s_token) * code[token][dim k]: the
+// token's scale is folded into its probability, the zero-points are summed separately (sum_n p_n
+// z_n is the same for every dim).  A unit's 32-bit words hold two consecutive tokens each, the
+// even one in the low half, and the probabilities come as fp16 pairs of the same two tokens, so
+// that one v_dot2_f32_f16 does both tokens of a dim with an fp32 accumulator.  A code needs no
+// conversion: masked in place it IS an fp16 number -- a denormal, code * 2^-24 when it sits in
+// bits 0.. of its half, code * 2^(-24 + shift) further up -- so a pair of codes costs one AND
+// (plus one shift per word for the fields beyond the mantissa), and each accumulator is scaled
+// back by its power of two once, at the end (vq_unscale).
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float dot2(uint32_t p_pair, uint32_t code_pair, float acc) {
+  f16x2 a, b;
+  __builtin_memcpy(&a, &p_pair, 4);
+  __builtin_memcpy(&b, &code_pair, 4);
+  return __builtin_amdgcn_fdot2(a, b, acc, false);
+}
+
+template <int G>
+struct Pairs {
+  uint32_t v[G];
+};
+template <int G>
+__device__ __forceinline__ Pairs<G> pairs_read(uint32_t addr) {
+  const Heads<G> f = lut_read<G>(addr);
+  Pairs<G> p;
+#pragma unroll
+  for (int h = 0; h < G; ++h) p.v[h] = f2u(f.v[h]);
+  return p;
+}
+
+// The lane's value with that of its neighbour lane (lane ^ 1), as an fp16 pair (this lane's in
+// the low half), round to nearest: called by the lanes that hold the probabilities of tokens
+// n (even lanes) and n + 1; the even lanes store the result.
+__device__ __forceinline__ uint32_t pack_with_neighbour(float x) {
+  const float other = u2f(static_cast<uint32_t>(
+      __builtin_amdgcn_update_dpp(0, static_cast<int>(f2u(x)), 0xB1 /* quad_perm(1,0,3,2) */, 0xf, 0xf, true)));
+  const __half2 h = __floats2half2_rn(x, other);
+  return *reinterpret_cast<const uint32_t*>(&h);
+}
+
+// Power of two an accumulator of dim k (of the lane's 8) is multiplied with at the end: undoes
+// the position of the dim's field above bit 0 of its half, and the 2^-24 of fp16 denormals.
+template <int VB>
+__device__ __forceinline__ constexpr float vq_unscale(int k) {
+  // 4 bits: fields of dims 0-3 (or 4-7) at bits 0, 4, 8, 12 of a half; 8 and 12 are read after a shift by 8
+  // 2 bits: fields of dims 0-7 at bits 0, 2, ..., 14; 10, 12, 14 are read after a shift by 10
+  const int shift = VB == 4 ? ((k & 1) ? 4 : 0) : (k < 5 ? 2 * k : 2 * (k - 5));
+  return static_cast<float>(1 << (24 - shift));
+}
+
+// One unit: `pp` is the LDS address of the fp16 probability pairs [token pair][G] of the unit's
+// first token pair.
 template <int G, int VB>
-__device__ __forceinline__ void consume_quantized(const uint4& u, int tok0, uint32_t pw, float (&acc)[G][8]) {
+__device__ __forceinline__ void consume_quantized(const uint4& u, uint32_t pp, float (&acc)[G][8]) {
   const uint32_t w4[4] = {u.x, u.y, u.z, u.w};
   if constexpr (VB == 4) {
-    // dword i = token tok0 + i; nibble k = dim k.  Even nibbles land in the bytes of (d & 0x0f0f0f0f),
-    // odd ones in the bytes of ((d >> 4) & 0x0f0f0f0f); one v_cvt_f32_ubyteN each.
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const Heads<G> p = lut_read<G>(pw + (tok0 + i) * (G * 4));
-      const uint32_t ev = w4[i] & 0x0f0f0f0fu, od = (w4[i] >> 4) & 0x0f0f0f0fu;
-      const float v[8] = {byte_to_float<0>(ev), byte_to_float<0>(od), byte_to_float<1>(ev), byte_to_float<1>(od),
-                          byte_to_float<2>(ev), byte_to_float<2>(od), byte_to_float<3>(ev), byte_to_float<3>(od)};
+    for (int tp = 0; tp < 2; ++tp) {
+      const Pairs<G> p = pairs_read<G>(pp + tp * (G * 4));
 #pragma unroll
-      for (int k = 0; k < 8; ++k)
+      for (int dh = 0; dh < 2; ++dh) {
+        const uint32_t d = w4[2 * tp + dh], e = d >> 8;
+        const uint32_t f[4] = {d & 0x000f000fu, d & 0x00f000f0u, e & 0x000f000fu, e & 0x00f000f0u};
 #pragma unroll
-        for (int h = 0; h < G; ++h) acc[h][k] = fmaf(p.v[h], v[k], acc[h][k]);
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+          for (int h = 0; h < G; ++h) acc[h][4 * dh + k] = dot2(p.v[h], f[k], acc[h][4 * dh + k]);
+      }
     }
   } else {
     static_assert(VB == 2, "value bits");
-    // dword i = tokens tok0 + 2i (low half) and tok0 + 2i + 1 (high half); 2-bit field k = dim k.
-    // (d >> 2k) & 0x03030303 puts dims k and k+4 of both tokens into the four bytes.
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const Heads<G> p0 = lut_read<G>(pw + (tok0 + 2 * i) * (G * 4));
-      const Heads<G> p1 = lut_read<G>(pw + (tok0 + 2 * i + 1) * (G * 4));
+    for (int tp = 0; tp < 4; ++tp) {
+      const Pairs<G> p = pairs_read<G>(pp + tp * (G * 4));
+      const uint32_t d = w4[tp], e = d >> 10;
+      const uint32_t f[8] = {d & 0x00030003u, d & 0x000c000cu, d & 0x00300030u, d & 0x00c000c0u, d & 0x03000300u,
+                             e & 0x00030003u, e & 0x000c000cu, e & 0x00300030u};
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const uint32_t m = (w4[i] >> (2 * k)) & 0x03030303u;
-        const float a0 = byte_to_float<0>(m), a4 = byte_to_float<1>(m);   // token 2i  : dims k, k+4
-        const float b0 = byte_to_float<2>(m), b4 = byte_to_float<3>(m);   // token 2i+1: dims k, k+4
+      for (int k = 0; k < 8; ++k)
 #pragma unroll
-        for (int h = 0; h < G; ++h) {
-          acc[h][k] = fmaf(p1.v[h], b0, fmaf(p0.v[h], a0, acc[h][k]));
-          acc[h][k + 4] = fmaf(p1.v[h], b4, fmaf(p0.v[h], a4, acc[h][k + 4]));
-        }
-      }
+        for (int h = 0; h < G; ++h) acc[h][k] = dot2(p.v[h], f[k], acc[h][k]);
     }
   }
 }
@@ -767,14 +809,17 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
     for (int t = 0; t < 8; ++t) {
       const float p = dead ? 0.f : __builtin_amdgcn_exp2f(sc[t] - m_new);
       psum += p;
-      float pv = p;
       if constexpr (kQuantV) {
-        // V~ = code * s + z (Section 2): fold s into the probability, collect p * z
+        // V~ = code * s + z (Section 2): fold s into the probability, collect p * z; the
+        // probabilities of tokens 2m, 2m + 1 (neighbour lanes) go to LDS as one fp16 pair
         const __half2 sz = *reinterpret_cast<const __half2*>(&vpar[t]);
-        pv = p * __low2float(sz);
         zsum = fmaf(p, __high2float(sz), zsum);
+        const uint32_t pr = pack_with_neighbour(p * __low2float(sz));
+        if (owner && (col & 1) == 0)
+          *(PQ_LDS uint32_t*)static_cast<uintptr_t>(pw_addr + ((t * 8 + (col >> 1)) * G + my_head) * 4) = pr;
+      } else {
+        if (owner) *(PQ_LDS float*)static_cast<uintptr_t>(pw_addr + ((t * 16 + col) * G + my_head) * 4) = p;
       }
-      if (owner) *(PQ_LDS float*)static_cast<uintptr_t>(pw_addr + ((t * 16 + col) * G + my_head) * 4) = pv;
     }
     if constexpr (kQuantV) z_run = fmaf(z_run, alpha, zsum);
     l_run = fmaf(l_run, alpha, psum);
@@ -807,7 +852,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
       // unit k of the page = tokens kTokPerLoad * k + (16 / VB) * row ..; refilled with the next page's unit k
 #pragma unroll
       for (int k = 0; k < kVLoads; ++k) {
-        consume_quantized<G, VB>(vq[k], kTokPerLoad * k + (16 / VB) * row, pw_addr, acc);
+        consume_quantized<G, VB>(vq[k], pw_addr + ((kTokPerLoad * k + (16 / VB) * row) >> 1) * (G * 4), acc);
         vq[k] = buf_load16<kAuxStream>(rv_nxt, voff_vq, k * 1024);
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -844,7 +889,10 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
     for (int h = 0; h < G; ++h) {
       float t[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) t[e] = sum_rows(acc[h][e]);
+      for (int e = 0; e < 8; ++e) {
+        t[e] = sum_rows(acc[h][e]);
+        if constexpr (kQuantV) t[e] *= vq_unscale<VB>(e);
+      }
       if (row == 0) {
         float4* dst = reinterpret_cast<float4*>(red_acc(wave) + h * kHeadDim + col * 8);
         dst[0] = make_float4(t[0], t[1], t[2], t[3]);

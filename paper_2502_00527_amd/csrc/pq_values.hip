@@ -80,9 +80,16 @@ __global__ __launch_bounds__(256) void pq_encode_values_kernel(const ValueArgs a
       field |= static_cast<uint32_t>(q) << (VB * e);
     }
     if (!valid) field = 0;
-    uint8_t* unit = dst + ((tok / T) * 16 + sl) * 16 + (tok % T) * VB;
-    if constexpr (VB == 4) *reinterpret_cast<uint32_t*>(unit) = field;
-    else *reinterpret_cast<uint16_t*>(unit) = static_cast<uint16_t>(field);
+    // A unit's 32-bit words hold two consecutive tokens each, the even one in the low half:
+    // 4-bit codes word 2 * pair + (dims 0-3 | dims 4-7), 2-bit codes word pair (all 8 dims).
+    uint8_t* unit = dst + ((tok / T) * 16 + sl) * 16;
+    const int pair = (tok % T) >> 1, half = tok & 1;
+    if constexpr (VB == 4) {
+      *reinterpret_cast<uint16_t*>(unit + (2 * pair) * 4 + half * 2) = static_cast<uint16_t>(field);
+      *reinterpret_cast<uint16_t*>(unit + (2 * pair + 1) * 4 + half * 2) = static_cast<uint16_t>(field >> 16);
+    } else {
+      *reinterpret_cast<uint16_t*>(unit + pair * 4 + half * 2) = static_cast<uint16_t>(field);
+    }
     if (sl == 0)
       a.vparams[ph * kGroup + tok] =
           valid ? (static_cast<uint32_t>(__half_as_ushort(sh)) | (static_cast<uint32_t>(__half_as_ushort(zh)) << 16)) : 0u;

@@ -52,26 +52,29 @@ def test_error_halves_per_bit():
 
 
 def test_value_pack_layout_by_hand():
-    """4 bits: token i of a unit is bytes [4i, 4i+4), dim k its nibble k (low nibble first).
-    2 bits: token i is bytes [2i, 2i+2), dim k the 2-bit field k.  Units: [token block][dim slice]."""
+    """Units: [token block][dim slice][16 bytes = four little-endian 32-bit words].  A word holds two
+    consecutive tokens, the even one in bits 0-15 and the odd one in bits 16-31, dims upward from
+    bit 0.  4 bits: word 2 * pair + (dims 0-3 | dims 4-7); 2 bits: word pair, all 8 dims of the slice."""
     L, H, d, g = 130, 1, 16, 128
     rng = np.random.default_rng(23)
     c4 = rng.integers(0, 16, (L, H, d))
     p4 = cache_format.pack_value_page_stream(c4, 4, g)
     assert p4.shape == (2, 1, 32, 2, 16)
-    n, dim = 7, 13                                     # token block 1, token 3 of it; slice 1, dim 5 of it
-    byte = p4[0, 0, n // 4, dim // 8, (n % 4) * 4 + (dim % 8) // 2]
-    assert (byte >> (4 * (dim % 2))) & 15 == c4[n, 0, dim]
-    n = 129                                            # page 1, token 1: block 0, token 1 of it
-    byte = p4[1, 0, 0, 0, 4 + 1]
-    assert byte == (c4[n, 0, 2] | (c4[n, 0, 3] << 4))
+    n, dim = 7, 13            # token block 1, token 3 of it = pair 1, odd; slice 1, dim 5 of it = upper dims, field 1
+    word = int.from_bytes(bytes(p4[0, 0, 1, 1, 12:16]), "little")          # word 2 * 1 + 1 = 3
+    assert (word >> (16 + 4 * 1)) & 15 == c4[n, 0, dim]
+    assert (word >> (4 * 3)) & 15 == c4[6, 0, 15]                           # the even token of the pair, dim 7 of the slice
+    n = 129                   # page 1, token 1: block 0, pair 0, odd
+    w0 = int.from_bytes(bytes(p4[1, 0, 0, 0, 0:4]), "little")
+    assert w0 == sum(int(c4[128, 0, f]) << (4 * f) for f in range(4)) | sum(int(c4[129, 0, f]) << (16 + 4 * f) for f in range(4))
     assert not p4[1, 0, 1:].any() and not p4[1, 0, 0, :, 8:].any()    # slots past token 129 are zero
     c2 = rng.integers(0, 4, (L, H, d))
     p2 = cache_format.pack_value_page_stream(c2, 2, g)
     assert p2.shape == (2, 1, 16, 2, 16)
-    n, dim = 21, 10                                    # block 2 (8 tokens per unit), token 5; slice 1, dim 2
-    half = p2[0, 0, 2, 1, 10] | (p2[0, 0, 2, 1, 11] << 8)
-    assert (half >> (2 * 2)) & 3 == c2[n, 0, dim]
+    n, dim = 21, 10           # block 2 (8 tokens per unit), token 5 = pair 2, odd; slice 1, dim 2
+    word = int.from_bytes(bytes(p2[0, 0, 2, 1, 8:12]), "little")            # word 2
+    assert (word >> (16 + 2 * 2)) & 3 == c2[n, 0, dim]
+    assert (word >> (2 * 7)) & 3 == c2[20, 0, 15]
     for bits, c in ((4, c4), (2, c2)):
         np.testing.assert_array_equal(cache_format.unpack_value_pages(
             cache_format.pack_value_page_stream(c, bits, g), L, bits), c)
