@@ -67,7 +67,6 @@
  * so the lookup table of Section 3.3 is rebuilt from (s, z) for every group (the appendix listing
  * does the same from "tscale" and "tmn").  The parameter block of a page doubles:
  *   params pool : [page][kv_head][2][pair P]{fp16 s, fp16 z}   radius parameters, then angle parameters
- * Available for (r, t) = (4, 4) and (3, 3).
  */
 #ifndef POLARQUANT_H
 #define POLARQUANT_H
@@ -100,7 +99,7 @@ typedef enum {
  * Supported: head_dim 128; (r_bits, t_bits) with r + t in {6, 8}, 2 <= r, t <= 5
  * -- (4,4) and (3,3) are the paper's main settings, the others its bit
  * allocation ablation (Section 6.1); group_tokens 128; any n_kv_heads >= 1;
- * angle_quantizer PQ_ANGLE_UNIFORM, or PQ_ANGLE_GROUPED with (4,4) or (3,3). */
+ * angle_quantizer PQ_ANGLE_UNIFORM or PQ_ANGLE_GROUPED. */
 typedef struct {
   int32_t head_dim;         /* d */
   int32_t r_bits;           /* radius bits r */
@@ -182,8 +181,7 @@ int pq_encode_values(const pq_layout* layout, int32_t v_bits, const void* values
  *   v_pool, v_bits, v_params_pool
  *                 v_bits 16: v_pool is the fp16 value pool, v_params_pool is ignored (NULL);
  *                 v_bits 4 or 2: v_pool is the quantized value pool and v_params_pool its
- *                 parameter pool (built for (r_bits, t_bits) = (4,4) and (3,3), either angle
- *                 quantizer)
+ *                 parameter pool
  *   n_pool_pages  pool size in pages; a block-table entry outside [0, n_pool_pages)
  *                 makes that page count as masked (no read happens)
  *   sm_scale      softmax scale (1/sqrt(d) for standard attention)

@@ -17,7 +17,8 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libpolarquant.so")
-SOURCES = ["pq_api.hip", "pq_encode.hip", "pq_values.hip", "pq_decode.hip", "pq_decode_vq.hip", "pq_decode_ga.hip", "pq_decode_ga_vq.hip", "pq_decode_roles.hip", "pq_decode_roles_grid.hip"]
+SOURCES = ["pq_api.hip", "pq_encode.hip", "pq_values.hip", "pq_decode.hip", "pq_decode_partials.hip",
+           "pq_decode_partials_ga.hip", "pq_decode_roles.hip", "pq_decode_roles_grid.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

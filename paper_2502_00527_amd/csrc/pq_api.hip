@@ -20,8 +20,7 @@ bool layout_supported(const pq_layout* l) {
   if (l->head_dim != kHeadDim || l->group_tokens != kGroup || l->n_kv_heads < 1) return false;
   const int r = l->r_bits, t = l->t_bits, w = r + t;
   if (r < 2 || r > 5 || t < 2 || t > 5) return false;
-  if (l->angle_quantizer == PQ_ANGLE_GROUPED) return r == t && (r == 4 || r == 3);
-  if (l->angle_quantizer != PQ_ANGLE_UNIFORM) return false;
+  if (l->angle_quantizer != PQ_ANGLE_UNIFORM && l->angle_quantizer != PQ_ANGLE_GROUPED) return false;
   return w == 6 || w == 8;
 }
 

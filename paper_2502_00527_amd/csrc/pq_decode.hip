@@ -12,6 +12,7 @@
 #define PQ_USE_ROLES 1
 #endif
 
+
 // Scratch of pq_decode_attention_static: the chunk partials live here instead of in a
 // caller-supplied workspace.  One copy per GPU, at its own address on each.
 static __device__ __align__(256) unsigned char scratch[PQ_STATIC_SCRATCH_BYTES];
@@ -88,18 +89,30 @@ __global__ __launch_bounds__(kMergeThreads) void pq_decode_merge_kernel(
   }
 }
 
-template <int RB, int TB>
-hipError_t launch_scores(int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st) {
-#define PQ_LAUNCH_SCORES(GG)                                                                            \
-  if (qdt == PQ_F16) hipLaunchKernelGGL((pq_score_keys_kernel<GG, RB, TB, __half>), grid, dim3(kThreads), 0, st, a); \
-  else hipLaunchKernelGGL((pq_score_keys_kernel<GG, RB, TB, float>), grid, dim3(kThreads), 0, st, a)
+template <int RB, int TB, bool GA>
+bool launch_scores_g(int G, const DecodeArgs& a, dim3 grid, hipStream_t st) {
+  const dim3 block(kThreads);
   switch (G) {
-    case 1: PQ_LAUNCH_SCORES(1); break;
-    case 2: PQ_LAUNCH_SCORES(2); break;
-    default: PQ_LAUNCH_SCORES(4); break;
+    case 1: hipLaunchKernelGGL((pq_score_keys_kernel<1, RB, TB, GA>), grid, block, 0, st, a); return true;
+    case 2: hipLaunchKernelGGL((pq_score_keys_kernel<2, RB, TB, GA>), grid, block, 0, st, a); return true;
+    case 4: hipLaunchKernelGGL((pq_score_keys_kernel<4, RB, TB, GA>), grid, block, 0, st, a); return true;
+    default: return false;
   }
-#undef PQ_LAUNCH_SCORES
-  return hipGetLastError();
+}
+template <bool GA>
+bool launch_scores_rt(int rt, int G, const DecodeArgs& a, dim3 grid, hipStream_t st) {
+  switch (rt) {
+    case 44: return launch_scores_g<4, 4, GA>(G, a, grid, st);
+    case 33: return launch_scores_g<3, 3, GA>(G, a, grid, st);
+    case 53: return launch_scores_g<5, 3, GA>(G, a, grid, st);
+    case 35: return launch_scores_g<3, 5, GA>(G, a, grid, st);
+    case 42: return launch_scores_g<4, 2, GA>(G, a, grid, st);
+    case 24: return launch_scores_g<2, 4, GA>(G, a, grid, st);
+    default: return false;
+  }
+}
+bool launch_scores(int rt, bool grouped, int G, const DecodeArgs& a, dim3 grid, hipStream_t st) {
+  return grouped ? launch_scores_rt<true>(rt, G, a, grid, st) : launch_scores_rt<false>(rt, G, a, grid, st);
 }
 
 // Which attention kernel a launch gets.  The role-specialised kernel, whose work-groups share
@@ -132,10 +145,16 @@ int balanced_groups(const pq_layout* l, int32_t n_seqs, int32_t max_seq_len) {
                                             (bound + kBalancedMinPages - 1) / kBalancedMinPages));
 }
 
-AttentionKernel choose_attention_kernel(const pq_layout* l, int32_t v_bits, int32_t n_seqs, int32_t max_seq_len) {
+AttentionKernel choose_attention_kernel(const pq_layout* l, int32_t v_bits, int32_t n_seqs, int32_t n_q_heads,
+                                        int32_t max_seq_len) {
   const int64_t max_pages = (static_cast<int64_t>(max_seq_len) + kGroup - 1) / kGroup;
   const int64_t bound = static_cast<int64_t>(n_seqs) * l->n_kv_heads * (max_pages + kBalancedUnitCost);
-  if (PQ_USE_ROLES && l->angle_quantizer == PQ_ANGLE_UNIFORM && v_bits == 16 && n_seqs <= kBalancedMaxSeqs &&
+  // Quantized values make the launch arithmetic-bound, and with 4 query heads per KV head most of
+  // that arithmetic is scoring: wavefronts that all score and aggregate use the four SIMDs evenly,
+  // specialised ones leave two of them short (measured at the GQA shape, 4-bit values: 150 against
+  // 178 us; with 1 or 2 heads per KV head the specialised kernel wins, 61 against 64 us at the MHA shape).
+  const bool roles_fit = v_bits == 16 || n_q_heads / l->n_kv_heads <= 2;
+  if (PQ_USE_ROLES && l->angle_quantizer == PQ_ANGLE_UNIFORM && roles_fit && n_seqs <= kBalancedMaxSeqs &&
       bound < (int64_t{1} << 31) && balanced_groups(l, n_seqs, max_seq_len) >= 256)
     return AttentionKernel::kRoles;
   return AttentionKernel::kPartials;
@@ -168,28 +187,6 @@ Workspace carve_workspace(void* base, const pq_layout* l, int32_t n_seqs, int32_
   const size_t words = units + static_cast<size_t>(balanced_groups(l, n_seqs, max_seq_len)) + units;   // per unit, per segment slot
   w.bytes = acc_bytes + ml_bytes + round256(words * sizeof(uint64_t));
   return w;
-}
-
-template <int G, int RB, int TB>
-hipError_t launch_partials(const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st) {
-  const bool sc = a.scores != nullptr;
-  if (qdt == PQ_F16) {
-    if (sc) hipLaunchKernelGGL((pq_decode_partials_kernel<G, RB, TB, __half, true, 16>), grid, dim3(kThreads), 0, st, a);
-    else    hipLaunchKernelGGL((pq_decode_partials_kernel<G, RB, TB, __half, false, 16>), grid, dim3(kThreads), 0, st, a);
-  } else {
-    if (sc) hipLaunchKernelGGL((pq_decode_partials_kernel<G, RB, TB, float, true, 16>), grid, dim3(kThreads), 0, st, a);
-    else    hipLaunchKernelGGL((pq_decode_partials_kernel<G, RB, TB, float, false, 16>), grid, dim3(kThreads), 0, st, a);
-  }
-  return hipGetLastError();
-}
-
-template <int RB, int TB>
-hipError_t launch_partials_g(int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st) {
-  switch (G) {
-    case 1: return launch_partials<1, RB, TB>(a, qdt, grid, st);
-    case 2: return launch_partials<2, RB, TB>(a, qdt, grid, st);
-    default: return launch_partials<4, RB, TB>(a, qdt, grid, st);
-  }
 }
 
 // cos / sin of the centre of every angle bin of the uniform grid over [-pi, pi) (Section 3.2
@@ -280,7 +277,6 @@ int decode_launch(const pq_layout* layout, const void* q, pq_dtype q_dtype, int3
     return PQ_ERR_INVALID_ARG;
   const int rt = layout->r_bits * 10 + layout->t_bits;
   const bool grouped = layout->angle_quantizer == PQ_ANGLE_GROUPED;
-  if ((grouped || v_bits != 16) && rt != 44 && rt != 33) return PQ_ERR_UNSUPPORTED;   // built for the two main settings
 
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return PQ_ERR_WORKSPACE;
   const Workspace ws = carve_workspace(workspace, layout, n_seqs, n_q_heads, max_seq_len);
@@ -312,6 +308,7 @@ int decode_launch(const pq_layout* layout, const void* q, pq_dtype q_dtype, int3
   a.max_seq_len = max_seq_len;
   a.pages_per_chunk = plan.pages_per_chunk;
   a.n_chunks = plan.n_chunks;
+  a.q_is_f32 = q_dtype == PQ_F32 ? 1 : 0;
   a.scale_log2 = static_cast<float>(static_cast<double>(sm_scale) * 1.4426950408889634074);
   fill_angle_tables(a, layout->t_bits);
 
@@ -322,7 +319,7 @@ int decode_launch(const pq_layout* layout, const void* q, pq_dtype q_dtype, int3
   // the units are few and each would be shared by more work-groups than one arrival word takes
   // well (one long sequence), or when only the partials are asked for: then one work-group per
   // chunk, and the merge kernel.
-  const bool roles = choose_attention_kernel(layout, v_bits, n_seqs, max_seq_len) == AttentionKernel::kRoles;
+  const bool roles = choose_attention_kernel(layout, v_bits, n_seqs, n_q_heads, max_seq_len) == AttentionKernel::kRoles;
   const int n_balanced = balanced_groups(layout, n_seqs, max_seq_len);
   const bool balanced = roles && out != nullptr && static_cast<int64_t>(n_seqs) * layout->n_kv_heads * kArriveFan >= n_balanced;
 #ifdef PQ_FORCE_GRID
@@ -338,25 +335,16 @@ int decode_launch(const pq_layout* layout, const void* q, pq_dtype q_dtype, int3
     const int left = group_total - head0;
     const int G = left >= 4 ? 4 : (left >= 2 ? 2 : 1);
     a.head0 = head0;
+    bool found;
     if (roles) {
-      e = a.grid_mode ? launch_attention_roles_grid(rt, G, a, q_dtype, static_cast<int>(grid.x * grid.y * grid.z), stream)
-                      : launch_attention_roles(rt, G, a, q_dtype, n_balanced, stream);
-    } else if (grouped) {
-      e = v_bits == 16 ? launch_partials_ga(rt, G, a, q_dtype, grid, stream)
-                       : launch_partials_ga_vq(rt, G, v_bits, a, q_dtype, grid, stream);
-    } else if (v_bits != 16) {
-      e = launch_partials_vq(rt, G, v_bits, a, q_dtype, grid, stream);
+      found = a.grid_mode ? launch_attention_roles_grid(rt, G, v_bits, a, static_cast<int>(grid.x * grid.y * grid.z), stream)
+                          : launch_attention_roles(rt, G, v_bits, a, n_balanced, stream);
     } else {
-      switch (rt) {
-        case 44: e = launch_partials_g<4, 4>(G, a, q_dtype, grid, stream); break;
-        case 33: e = launch_partials_g<3, 3>(G, a, q_dtype, grid, stream); break;
-        case 53: e = launch_partials_g<5, 3>(G, a, q_dtype, grid, stream); break;
-        case 35: e = launch_partials_g<3, 5>(G, a, q_dtype, grid, stream); break;
-        case 42: e = launch_partials_g<4, 2>(G, a, q_dtype, grid, stream); break;
-        case 24: e = launch_partials_g<2, 4>(G, a, q_dtype, grid, stream); break;
-        default: return PQ_ERR_UNSUPPORTED;   // not reached: layout_supported() admits exactly these
-      }
+      found = grouped ? launch_attention_partials_ga(rt, G, v_bits, a, grid, stream)
+                      : launch_attention_partials(rt, G, v_bits, a, grid, stream);
     }
+    if (!found) return PQ_ERR_UNSUPPORTED;   // not reached: layout_supported() admits what is built
+    e = hipGetLastError();
     head0 += G;
   }
   if (e != hipSuccess) return record_hip_error(e);
@@ -388,7 +376,7 @@ extern "C" int pq_decode_partials(const pq_layout* layout, const void* q, pq_dty
 extern "C" const char* pq_decode_kernel_name(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
                                              int32_t max_seq_len, int32_t v_bits) {
   if (check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len) != PQ_OK) return "";
-  return choose_attention_kernel(layout, v_bits, n_seqs, max_seq_len) == AttentionKernel::kRoles
+  return choose_attention_kernel(layout, v_bits, n_seqs, n_q_heads, max_seq_len) == AttentionKernel::kRoles
              ? "pq_decode_roles_kernel" : "pq_decode_partials_kernel";
 }
 
@@ -455,10 +443,16 @@ extern "C" int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_
   if (n_pool_pages <= 0 || max_pages_per_seq <= 0 || scores_stride < max_seq_len) return PQ_ERR_INVALID_ARG;
   const int64_t need_pages = (static_cast<int64_t>(max_seq_len) + kGroup - 1) / kGroup;
   if (need_pages > max_pages_per_seq) return PQ_ERR_INVALID_ARG;
-  if (reinterpret_cast<uintptr_t>(residual_keys) & 15u) return PQ_ERR_INVALID_ARG;
+  // the pools are read with 128-bit loads
+  if ((reinterpret_cast<uintptr_t>(codes_pool) | reinterpret_cast<uintptr_t>(params_pool) |
+       reinterpret_cast<uintptr_t>(residual_keys)) & 15u)
+    return PQ_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(block_table) | reinterpret_cast<uintptr_t>(seq_lens) | reinterpret_cast<uintptr_t>(scores)) & 3u)
+    return PQ_ERR_INVALID_ARG;
   const ChunkPlan plan = plan_chunks(n_seqs, layout->n_kv_heads, max_seq_len);
   DecodeArgs a = {};
   a.q = q;
+  a.q_is_f32 = q_dtype == PQ_F32 ? 1 : 0;
   a.residual = static_cast<const __half*>(residual_keys);
   a.codes = static_cast<const uint8_t*>(codes_pool);
   a.params = static_cast<const uint32_t*>(params_pool);
@@ -484,21 +478,9 @@ extern "C" int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_
     const int left = group_total - head0;
     const int G = left >= 4 ? 4 : (left >= 2 ? 2 : 1);
     a.head0 = head0;
-    if (layout->angle_quantizer == PQ_ANGLE_GROUPED) {
-      e = launch_scores_ga(layout->r_bits * 10 + layout->t_bits, G, a, q_dtype, grid, stream);
-      if (e == hipErrorInvalidValue) return PQ_ERR_UNSUPPORTED;
-      head0 += G;
-      continue;
-    }
-    switch (layout->r_bits * 10 + layout->t_bits) {
-      case 44: e = launch_scores<4, 4>(G, a, q_dtype, grid, stream); break;
-      case 33: e = launch_scores<3, 3>(G, a, q_dtype, grid, stream); break;
-      case 53: e = launch_scores<5, 3>(G, a, q_dtype, grid, stream); break;
-      case 35: e = launch_scores<3, 5>(G, a, q_dtype, grid, stream); break;
-      case 42: e = launch_scores<4, 2>(G, a, q_dtype, grid, stream); break;
-      case 24: e = launch_scores<2, 4>(G, a, q_dtype, grid, stream); break;
-      default: return PQ_ERR_UNSUPPORTED;
-    }
+    if (!launch_scores(layout->r_bits * 10 + layout->t_bits, layout->angle_quantizer == PQ_ANGLE_GROUPED, G, a, grid, stream))
+      return PQ_ERR_UNSUPPORTED;           // not reached: layout_supported() admits what is built
+    e = hipGetLastError();
     head0 += G;
   }
   if (e != hipSuccess) return record_hip_error(e);

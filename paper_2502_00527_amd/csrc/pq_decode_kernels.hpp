@@ -64,6 +64,7 @@ struct DecodeArgs {
   uint64_t* arrivals;       // one arrival word per (sequence, KV head), then one per segment slot
   int32_t min_pages;        // smallest share of a work-group, in pages
   int32_t unit_cost;        // what starting on a (sequence, KV head) costs a work-group, in pages
+  int32_t q_is_f32;         // the query is fp32 (else fp16)
   int32_t grid_mode;        // role-specialised kernel: one work-group per (KV head, sequence, chunk) instead
   int64_t scores_stride;
   int64_t n_pool_pages;
@@ -80,18 +81,12 @@ struct DecodeArgs {
   float sin_tab[kMaxAngleBins];
 };
 
-// Launches the attention kernel for quantized values (VB = 4 or 2); defined in pq_decode_vq.hip so
-// that the two sets of instantiations compile in parallel.  hipErrorInvalidValue if there is no
-// kernel for the combination.
-hipError_t launch_partials_vq(int rt, int G, int v_bits, const DecodeArgs& a, pq_dtype qdt, dim3 grid,
-                              hipStream_t st);
-// The attention and score-only kernels for the grouped angle quantizer (fp16 values; (r,t) =
-// (4,4) or (3,3)); defined in pq_decode_ga.hip.  hipErrorInvalidValue if there is no kernel.
-hipError_t launch_partials_ga(int rt, int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st);
-hipError_t launch_scores_ga(int rt, int G, const DecodeArgs& a, pq_dtype qdt, dim3 grid, hipStream_t st);
-// Grouped angle quantizer with quantized values; defined in pq_decode_ga_vq.hip.
-hipError_t launch_partials_ga_vq(int rt, int G, int v_bits, const DecodeArgs& a, pq_dtype qdt, dim3 grid,
-                                 hipStream_t st);
+// Launchers of the instantiation units (rt = 10 r + t).  They return false, and launch nothing,
+// if there is no kernel for the combination; launch errors are left to hipGetLastError().
+// pq_decode_partials.hip / pq_decode_partials_ga.hip: the attention kernel whose wavefronts
+// alternate between a score and a value phase, uniform angle grid / grouped angle quantizer.
+bool launch_attention_partials(int rt, int G, int v_bits, const DecodeArgs& a, dim3 grid, hipStream_t st);
+bool launch_attention_partials_ga(int rt, int G, int v_bits, const DecodeArgs& a, dim3 grid, hipStream_t st);
 
 namespace {
 
@@ -152,11 +147,12 @@ __device__ __forceinline__ void wave_lds_sync() {
 #ifndef PQ_RING_SETS
 #define PQ_RING_SETS 4
 #endif
-#ifndef PQ_WAVES_PER_EU
-#define PQ_WAVES_PER_EU 2
+// Quantized values: units in flight per wavefront.  With 4 instead of 8 a third wavefront per SIMD
+// fits without spills; measured, that is 5 % slower than two wavefronts with a whole page in flight.
+#ifndef PQ_VQ_RING
+#define PQ_VQ_RING 8
 #endif
-#define PQ_KERNEL_ATTR \
-  __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(PQ_WAVES_PER_EU, PQ_WAVES_PER_EU)))
+#define PQ_KERNEL_ATTR __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 // ---- streaming loads --------------------------------------------------------
 // Codes, parameters and values are read through buffer descriptors that cover
@@ -478,10 +474,17 @@ __device__ __forceinline__ void store_query_lds(float (*q_lds)[4], float2* trig,
     trig[tid - kHeadDim] = r.cs;
   }
 }
-template <int G, typename QT>
-__device__ __forceinline__ void load_query_lds(float (*q_lds)[4], float2* trig, const QT* qb, const DecodeArgs& a,
+// The G query heads from element `q_at` of a.q on; the query's type (fp16 / fp32) is a run-time
+// property of the call.
+template <int G>
+__device__ __forceinline__ QueryRegs<G> fetch_query(const DecodeArgs& a, int64_t q_at, int tid) {
+  return a.q_is_f32 ? fetch_query<G, float>(static_cast<const float*>(a.q) + q_at, a, tid)
+                    : fetch_query<G, __half>(static_cast<const __half*>(a.q) + q_at, a, tid);
+}
+template <int G>
+__device__ __forceinline__ void load_query_lds(float (*q_lds)[4], float2* trig, const DecodeArgs& a, int64_t q_at,
                                                int tid) {
-  store_query_lds<G>(q_lds, trig, fetch_query<G, QT>(qb, a, tid), tid);
+  store_query_lds<G>(q_lds, trig, fetch_query<G>(a, q_at, tid), tid);
 }
 
 // Table of the uniform angle grid (Section 3.3): T[j][a][h] = q_x[h][j] cos(theta~_a) + q_y[h][j]
@@ -579,7 +582,7 @@ __device__ __forceinline__ void build_group_table(uint32_t lut_w, uint32_t tpar,
   }
 }
 
-template <int G, int RB, int TB, typename QT, bool SCORES, int VB, bool GA = false>
+template <int G, int RB, int TB, int VB, bool GA>
 __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   constexpr int W = RB + TB;
   constexpr int UB = 2 * W;              // bytes per unit
@@ -700,7 +703,10 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   Unit<W / 2> cu[8];
   constexpr int kRingSets = PQ_RING_SETS;                          // register quads of 4 value rows in flight
   uint4 ring[kRingSets][4];                                        // fp16 values
-  uint4 vq[kQuantV ? kVLoads : 1];                                 // quantized values: the whole page's units
+  // quantized values: kVRing of the page's kVLoads units in flight; unit k sits in vq[k % kVRing]
+  // and is replaced, once consumed, by unit k + kVRing (of the next page beyond the last unit)
+  constexpr int kVRing = kVLoads < PQ_VQ_RING ? kVLoads : PQ_VQ_RING;
+  uint4 vq[kQuantV ? kVRing : 1];
   uint32_t vpar[8];                                                // quantized values: (scale, zero) of tokens 16 t + col
   const uint32_t voff_vq = lane * 16;                              // lane (row, col): token block row, dim slice col
   const uint32_t voff_vpar = col * 4;
@@ -715,7 +721,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
 #pragma unroll
       for (int t = 0; t < 8; ++t) vpar[t] = buf_load4<kAuxCached>(rvp_cur, voff_vpar, t * 64);
 #pragma unroll
-      for (int k = 0; k < kVLoads; ++k) vq[k] = buf_load16<kAuxStream>(rv_cur, voff_vq, k * 1024);
+      for (int k = 0; k < kVRing; ++k) vq[k] = buf_load16<kAuxStream>(rv_cur, voff_vq, k * 1024);
     } else {
 #pragma unroll
       for (int k = 0; k < kRingSets; ++k)
@@ -728,8 +734,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   // ---- table of the G query heads that share this KV head (Section 3.3) ----
   // (built while the first page's loads, issued above, are in flight)
   {
-    const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim;
-    load_query_lds<G, QT>(q_lds, trig, qb, a, tid);
+    load_query_lds<G>(q_lds, trig, a, (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim, tid);
     if constexpr (!GA) {
       __syncthreads();
       build_uniform_table<TB>(lut, q_lds, trig, tid, kThreads);
@@ -792,7 +797,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       const int tok = t * 16 + col;
-      if constexpr (SCORES) {
+      if (a.scores != nullptr) {
         if (owner && tok < nv_cur)
           a.scores[(static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0 + my_head) * a.scores_stride +
                    static_cast<int64_t>(pi) * kGroup + tok] = sc[t];
@@ -852,8 +857,9 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
       // unit k of the page = tokens kTokPerLoad * k + (16 / VB) * row ..; refilled with the next page's unit k
 #pragma unroll
       for (int k = 0; k < kVLoads; ++k) {
-        consume_quantized<G, VB>(vq[k], pw_addr + ((kTokPerLoad * k + (16 / VB) * row) >> 1) * (G * 4), acc);
-        vq[k] = buf_load16<kAuxStream>(rv_nxt, voff_vq, k * 1024);
+        consume_quantized<G, VB>(vq[k % kVRing], pw_addr + ((kTokPerLoad * k + (16 / VB) * row) >> 1) * (G * 4), acc);
+        if (k + kVRing < kVLoads) vq[k % kVRing] = buf_load16<kAuxStream>(rv_cur, voff_vq, (k + kVRing) * 1024);
+        else vq[k % kVRing] = buf_load16<kAuxStream>(rv_nxt, voff_vq, (k + kVRing - kVLoads) * 1024);
         __builtin_amdgcn_sched_barrier(0);
       }
     } else {
@@ -927,7 +933,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
 // ---- query-key scores only (the kernel the paper times in Section 5.2) ------------------
 // Same table, same page walk and same pair steps as the attention kernel, without softmax and
 // values: every wavefront scores its pages and stores the raw q . k~ of valid tokens.
-template <int G, int RB, int TB, typename QT, bool GA = false>
+template <int G, int RB, int TB, bool GA>
 __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArgs a) {
   constexpr int W = RB + TB;
   constexpr int UB = 2 * W;
@@ -989,8 +995,7 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
     for (int i = 0; i < 8; ++i) cu[i] = load_unit<W>(rc_cur, voff_codes, i * 16 * UB);
   }
   {
-    const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim;
-    load_query_lds<G, QT>(q_lds, trig, qb, a, tid);
+    load_query_lds<G>(q_lds, trig, a, (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim, tid);
     if constexpr (!GA) {
       __syncthreads();
       build_uniform_table<TB>(lut, q_lds, trig, tid, kThreads);

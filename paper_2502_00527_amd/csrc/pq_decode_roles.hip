@@ -1,6 +1,6 @@
-// Instantiations of the role-specialised attention kernel (fp16 values, uniform angle grid): the
-// kernels that share a launch out evenly and merge inside.  pq_decode_roles_grid.hip compiles this
-// file a second time for the one-work-group-per-chunk kernels.
+// Instantiations of the role-specialised attention kernel (uniform angle grid): the kernels that
+// share a launch out evenly and merge inside.  pq_decode_roles_grid.hip compiles this file a
+// second time for the one-work-group-per-chunk kernels.
 #include "pq_decode_roles.hpp"
 
 #ifndef PQ_ROLES_BALANCED
@@ -11,50 +11,39 @@
 namespace pq {
 namespace {
 
-template <int G, int RB, int TB, typename QT, bool SCORES>
-void launch_mode(const DecodeArgs& a, const dim3 grid, hipStream_t st) {
-  hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, QT, SCORES, PQ_ROLES_BALANCED>), grid, dim3(kRoleThreads), 0, st, a);
-}
-
-template <int G, int RB, int TB>
-void launch_one(const DecodeArgs& a, pq_dtype qdt, int n_wg, hipStream_t st) {
-  const dim3 grid(n_wg);
-  const bool sc = a.scores != nullptr;
-  if (qdt == PQ_F16) {
-    if (sc) launch_mode<G, RB, TB, __half, true>(a, grid, st);
-    else    launch_mode<G, RB, TB, __half, false>(a, grid, st);
-  } else {
-    if (sc) launch_mode<G, RB, TB, float, true>(a, grid, st);
-    else    launch_mode<G, RB, TB, float, false>(a, grid, st);
+template <int RB, int TB, int VB>
+bool launch_g(int G, const DecodeArgs& a, int n_wg, hipStream_t st) {
+  const dim3 grid(n_wg), block(kRoleThreads);
+  switch (G) {
+    case 1: hipLaunchKernelGGL((pq_decode_roles_kernel<1, RB, TB, VB, PQ_ROLES_BALANCED>), grid, block, 0, st, a); return true;
+    case 2: hipLaunchKernelGGL((pq_decode_roles_kernel<2, RB, TB, VB, PQ_ROLES_BALANCED>), grid, block, 0, st, a); return true;
+    case 4: hipLaunchKernelGGL((pq_decode_roles_kernel<4, RB, TB, VB, PQ_ROLES_BALANCED>), grid, block, 0, st, a); return true;
+    default: return false;
   }
 }
 
 template <int RB, int TB>
-bool launch_g(int G, const DecodeArgs& a, pq_dtype qdt, int grid, hipStream_t st) {
-  switch (G) {
-    case 1: launch_one<1, RB, TB>(a, qdt, grid, st); return true;
-    case 2: launch_one<2, RB, TB>(a, qdt, grid, st); return true;
-    case 4: launch_one<4, RB, TB>(a, qdt, grid, st); return true;
+bool launch_v(int v_bits, int G, const DecodeArgs& a, int n_wg, hipStream_t st) {
+  switch (v_bits) {
+    case 16: return launch_g<RB, TB, 16>(G, a, n_wg, st);
+    case 4: return launch_g<RB, TB, 4>(G, a, n_wg, st);
+    case 2: return launch_g<RB, TB, 2>(G, a, n_wg, st);
     default: return false;
   }
 }
 
 }  // namespace
 
-hipError_t PQ_ROLES_LAUNCH(int rt, int G, const DecodeArgs& a, pq_dtype qdt, int grid, hipStream_t st) {
-  bool ok = false;
+bool PQ_ROLES_LAUNCH(int rt, int G, int v_bits, const DecodeArgs& a, int n_wg, hipStream_t st) {
   switch (rt) {
-    case 44: ok = launch_g<4, 4>(G, a, qdt, grid, st); break;
-    case 33: ok = launch_g<3, 3>(G, a, qdt, grid, st); break;
-    case 53: ok = launch_g<5, 3>(G, a, qdt, grid, st); break;
-    case 35: ok = launch_g<3, 5>(G, a, qdt, grid, st); break;
-    case 42: ok = launch_g<4, 2>(G, a, qdt, grid, st); break;
-    case 24: ok = launch_g<2, 4>(G, a, qdt, grid, st); break;
-    default: break;
+    case 44: return launch_v<4, 4>(v_bits, G, a, n_wg, st);
+    case 33: return launch_v<3, 3>(v_bits, G, a, n_wg, st);
+    case 53: return launch_v<5, 3>(v_bits, G, a, n_wg, st);
+    case 35: return launch_v<3, 5>(v_bits, G, a, n_wg, st);
+    case 42: return launch_v<4, 2>(v_bits, G, a, n_wg, st);
+    case 24: return launch_v<2, 4>(v_bits, G, a, n_wg, st);
+    default: return false;
   }
-  if (!ok) return hipErrorInvalidValue;
-  return hipGetLastError();
 }
 
 }  // namespace pq
-

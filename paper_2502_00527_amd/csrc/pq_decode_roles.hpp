@@ -24,8 +24,10 @@ namespace pq {
 
 // n_wg work-groups; the first shares the launch out evenly and merges in the kernel, the second
 // expects n_wg = KV heads x sequences x chunks and leaves the chunks' partials in the workspace.
-hipError_t launch_attention_roles(int rt, int G, const DecodeArgs& a, pq_dtype qdt, int n_wg, hipStream_t st);
-hipError_t launch_attention_roles_grid(int rt, int G, const DecodeArgs& a, pq_dtype qdt, int n_wg, hipStream_t st);
+// Both return false if there is no kernel for ((r, t) = rt / 10, rt % 10; G; v_bits) -- nothing is
+// launched then -- and leave launch errors to hipGetLastError().
+bool launch_attention_roles(int rt, int G, int v_bits, const DecodeArgs& a, int n_wg, hipStream_t st);
+bool launch_attention_roles_grid(int rt, int G, int v_bits, const DecodeArgs& a, int n_wg, hipStream_t st);
 
 
 namespace {
@@ -86,7 +88,12 @@ __device__ __forceinline__ void rotate_priority(int turn) {
 // BAL: the launch is shared out evenly and merged in the kernel (pq_decode_sched.hpp); otherwise
 // one work-group per (KV head, sequence, chunk) and pq_decode_merge_kernel afterwards.  Two
 // kernels rather than a run-time switch: the second one carries none of the first one's code.
-template <int G, int RB, int TB, typename QT, bool SCORES, bool BAL>
+// VB: 16 = fp16 values, 4 / 2 = token-wise quantized values (the score wavefront then folds the
+// token's scale into its probability, sums the zero-point term and hands fp16 probability pairs
+// over; the value wavefront streams the page's units).  The query's type and whether raw scores
+// are stored are run-time switches (a.q_is_f32, a.scores): both touch a few instructions per
+// page and are not worth kernels of their own.
+template <int G, int RB, int TB, int VB, bool BAL>
 __global__ __launch_bounds__(kRoleThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
 void pq_decode_roles_kernel(const DecodeArgs a) {
   constexpr int W = RB + TB;
@@ -94,12 +101,16 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
   constexpr int NA = 1 << TB;
   constexpr int ROW = NA * 16;
   constexpr int kRing = 4;                               // quads of 4 value rows in flight
+  constexpr bool kQuantV = VB != 16;
+  constexpr int kVLoads = kQuantV ? kGroup * kHeadDim * VB / 8 / 1024 : 32;   // 1 KB wavefront loads per page of values
+  constexpr int kTokPerLoad = kGroup / kVLoads;
 
   __shared__ __attribute__((aligned(16))) uint8_t lut[kPairs * ROW];
-  __shared__ __attribute__((aligned(16))) float prob[kPairsOfWaves][2][kGroup * G];
+  // probabilities of a page: fp32 [token][G], or fp16 pairs [token pair][G] for quantized values
+  __shared__ __attribute__((aligned(16))) float prob[kPairsOfWaves][2][(kQuantV ? kGroup / 2 : kGroup) * G];
   __shared__ __attribute__((aligned(16))) float alpha_s[kPairsOfWaves][2][4];
   __shared__ __attribute__((aligned(16))) float red_acc[kPairsOfWaves][G][kHeadDim];
-  __shared__ float red_ml[kPairsOfWaves][G][2];
+  __shared__ float red_ml[kPairsOfWaves][G][3];                       // m, l, sum of p * zero-point
   __shared__ __attribute__((aligned(16))) float q_lds[kHeadDim][4];
   __shared__ float2 trig[kMaxAngleBins];
   __shared__ float res_sc[kGroup * G];
@@ -135,8 +146,7 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
     const int n_steps = (npg + kPairsOfWaves - 1) / kPairsOfWaves + 1;   // pair 0's page count, plus one step of skew
     const int res_page = (a.residual != nullptr && (L % kGroup) != 0) ? L / kGroup : -1;
     // the query is fetched first and the page ids next; both are under way together
-    const QT* qb = static_cast<const QT*>(a.q) + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim;
-    const QueryRegs<G> q_regs = fetch_query<G, QT>(qb, a, tid);
+    const QueryRegs<G> q_regs = fetch_query<G>(a, (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim, tid);
     PageIds pids;
     pids.start(a.block_table + static_cast<int64_t>(seq) * a.max_pages_per_seq + page0 + pair, a.n_pool_pages, n_p, lane);
 
@@ -145,9 +155,13 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
       const uint32_t lut_row0 = lds_addr(lut) + row * (kPairsPerUnit * ROW);
       const uint32_t voff_codes = (row * kGroup + col) * UB;
       const uint32_t voff_params = row * (kPairsPerUnit * 4);
-      float m_run = kNegInf, l_run = 0.f;
+      float m_run = kNegInf, l_run = 0.f, z_run = 0.f;
+      const uint32_t voff_vpar = col * 4;
 
-      auto page_setup = [&](int k, __amdgpu_buffer_rsrc_t& rc, __amdgpu_buffer_rsrc_t& rp, int& nv) {
+      // descriptors of the pair's k-th page: codes, radius parameters, value parameters (rvp: the
+      // {fp16 scale, fp16 zero} of its valid tokens, with quantized values)
+      auto page_setup = [&](int k, __amdgpu_buffer_rsrc_t& rc, __amdgpu_buffer_rsrc_t& rp, __amdgpu_buffer_rsrc_t& rvp,
+                            int& nv) {
         const int pid = pids.get(k, lane);
         const bool ok = pid >= 0;
         const int64_t ph = ok ? static_cast<int64_t>(pid) * a.n_kv_heads + kvh : 0;
@@ -155,16 +169,23 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
         const bool packed = ok && (page0 + pair + kPairsOfWaves * k) != res_page;
         rc = make_rsrc(a.codes + ph * kCodesBytes, packed ? kCodesBytes : 0u);
         rp = make_rsrc(a.params + ph * kPairs, packed ? kPairs * 4u : 0u);
+        if constexpr (kQuantV) rvp = make_rsrc(a.v_params + ph * kGroup, static_cast<uint32_t>(nv) * 4u);
+        else rvp = rp;
       };
 
       // the first page's parameters and codes are under way while the table is built
-      __amdgpu_buffer_rsrc_t rc_cur, rp_cur, rc_nxt, rp_nxt;
+      __amdgpu_buffer_rsrc_t rc_cur, rp_cur, rvp_cur, rc_nxt, rp_nxt, rvp_nxt;
       int nv_cur, nv_nxt;
-      page_setup(0, rc_cur, rp_cur, nv_cur);
+      page_setup(0, rc_cur, rp_cur, rvp_cur, nv_cur);
       uint4 praw[4];
+      uint32_t vpar[8];                                              // quantized values: (scale, zero) of tokens 16 t + col
       Unit<W / 2> cu[8];
 #pragma unroll
       for (int i = 0; i < 4; ++i) praw[i] = buf_load16<kAuxCached>(rp_cur, voff_params, i * 16);
+      if constexpr (kQuantV) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) vpar[t] = buf_load4<kAuxCached>(rvp_cur, voff_vpar, t * 64);
+      }
 #pragma unroll
       for (int i = 0; i < 8; ++i) cu[i] = load_unit<W>(rc_cur, voff_codes, i * 16 * UB);
 
@@ -186,7 +207,7 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
         if constexpr (BAL) rotate_priority(tier + t);
         if (t < n_p) {
           const int pi = page0 + pair + kPairsOfWaves * t;
-          page_setup(t + 1, rc_nxt, rp_nxt, nv_nxt);
+          page_setup(t + 1, rc_nxt, rp_nxt, rvp_nxt, nv_nxt);
           float sf[16], zz[16];
           unpack_radius_params(praw, sf, zz);
 #pragma unroll
@@ -211,7 +232,7 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
 #pragma unroll
           for (int k = 0; k < 8; ++k) {
             const int tok = k * 16 + col;
-            if constexpr (SCORES) {
+            if (a.scores != nullptr) {
               if (owner && tok < nv_cur)
                 a.scores[(static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0 + my_head) * a.scores_stride +
                          static_cast<int64_t>(pi) * kGroup + tok] = sc[k];
@@ -224,28 +245,45 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
           const bool dead = !(m_new > kNegInf);
           const float alpha = dead ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
           const uint32_t pw = lds_addr(prob[pair][t & 1]);
-          float psum = 0.f;
+          float psum = 0.f, zsum = 0.f;
 #pragma unroll
           for (int k = 0; k < 8; ++k) {
             const float p = dead ? 0.f : __builtin_amdgcn_exp2f(sc[k] - m_new);
             psum += p;
-            if (owner) *(PQ_LDS float*)static_cast<uintptr_t>(pw + ((k * 16 + col) * G + my_head) * 4) = p;
+            if constexpr (kQuantV) {
+              // V~ = code * s + z (Section 2): fold s into the probability, collect p * z; the
+              // probabilities of tokens 2m, 2m + 1 (neighbour lanes) go over as one fp16 pair
+              const __half2 sz = *reinterpret_cast<const __half2*>(&vpar[k]);
+              zsum = fmaf(p, __high2float(sz), zsum);
+              const uint32_t pr = pack_with_neighbour(p * __low2float(sz));
+              if (owner && (col & 1) == 0)
+                *(PQ_LDS uint32_t*)static_cast<uintptr_t>(pw + ((k * 8 + (col >> 1)) * G + my_head) * 4) = pr;
+            } else {
+              if (owner) *(PQ_LDS float*)static_cast<uintptr_t>(pw + ((k * 16 + col) * G + my_head) * 4) = p;
+            }
+          }
+          if constexpr (kQuantV) {
+            z_run = fmaf(z_run, alpha, zsum);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) vpar[k] = buf_load4<kAuxCached>(rvp_nxt, voff_vpar, k * 64);
           }
           l_run = fmaf(l_run, alpha, psum);
           m_run = m_new;
           if (owner && col == 0) alpha_s[pair][t & 1][my_head] = alpha;
-          rc_cur = rc_nxt; rp_cur = rp_nxt; nv_cur = nv_nxt;
+          rc_cur = rc_nxt; rp_cur = rp_nxt; rvp_cur = rvp_nxt; nv_cur = nv_nxt;
         }
         __syncthreads();                                               // hand buffer t % 2 to the value wavefront
       }
       const float l_tot = row_sum(l_run);
+      const float z_tot = kQuantV ? row_sum(z_run) : 0.f;
       if (owner && col == 0) {
         red_ml[pair][my_head][0] = m_run;
         red_ml[pair][my_head][1] = l_tot;
+        red_ml[pair][my_head][2] = z_tot;
       }
     } else {
       // =========================== VALUE wavefront ===========================
-      const uint32_t voff_values = row * (kHeadDim * 2) + col * 16;
+      const uint32_t voff_values = kQuantV ? lane * 16 : row * (kHeadDim * 2) + col * 16;
       float acc[G][8];
 #pragma unroll
       for (int h = 0; h < G; ++h)
@@ -258,17 +296,30 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
         const int64_t ph = ok ? static_cast<int64_t>(pid) * a.n_kv_heads + kvh : 0;
         const int nv = ok ? min(kGroup, L - (page0 + pair + kPairsOfWaves * k) * kGroup) : 0;
         rot = ok ? (pid * 13 + kvh * 5) & 31 : 0;
-        rv = make_rsrc(a.values + ph * (kGroup * kHeadDim), static_cast<uint32_t>(nv) * (kHeadDim * 2));
+        if constexpr (kQuantV) {
+          // whole units are read; codes of slots past the sequence end are zero bytes and meet a
+          // zero probability
+          rv = make_rsrc(reinterpret_cast<const uint8_t*>(a.values) + ph * (kGroup * kHeadDim * VB / 8),
+                         nv > 0 ? kGroup * kHeadDim * VB / 8 : 0u);
+        } else {
+          rv = make_rsrc(a.values + ph * (kGroup * kHeadDim), static_cast<uint32_t>(nv) * (kHeadDim * 2));
+        }
       };
       __amdgpu_buffer_rsrc_t rv_cur, rv_nxt;
       int rot_cur, rot_nxt;
       page_setup(0, rv_cur, rot_cur);
-      uint4 ring[kRing][4];
+      uint4 ring[kQuantV ? 1 : kRing][4];                            // fp16 values: rows in flight
+      uint4 vq[kQuantV ? kVLoads : 1];                               // quantized values: the page's units
+      if constexpr (kQuantV) {
 #pragma unroll
-      for (int k = 0; k < kRing; ++k)
+        for (int k = 0; k < kVLoads; ++k) vq[k] = buf_load16<kAuxStream>(rv_cur, voff_values, k * 1024);
+      } else {
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          ring[k][r] = buf_load16<kAuxStream>(rv_cur, voff_values, static_cast<uint32_t>((4 * k + r + rot_cur) & 31) * 1024u);
+        for (int k = 0; k < kRing; ++k)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            ring[k][r] = buf_load16<kAuxStream>(rv_cur, voff_values, static_cast<uint32_t>((4 * k + r + rot_cur) & 31) * 1024u);
+      }
 
       store_query_lds<G>(q_lds, trig, q_regs, tid);
       __syncthreads();
@@ -288,24 +339,35 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
 #pragma unroll
               for (int e = 0; e < 8; ++e) acc[h][e] *= al[h];
           }
-          const uint32_t pw_row = lds_addr(prob[pair][j & 1]) + row * (G * 4);
-          // all rows in flight have arrived before the page is taken up: the wavefront then issues its
+          // all loads in flight have arrived before the page is taken up: the wavefront then issues its
           // refills in a burst, row after row of one page (measured 2 % faster than waking up for every row)
           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
           __builtin_amdgcn_sched_barrier(0);
+          if constexpr (kQuantV) {
+            // unit k of the page = tokens kTokPerLoad * k + (16 / VB) * row ..; refilled with the next page's unit k
+            const uint32_t pp = lds_addr(prob[pair][j & 1]) + (((16 / VB) * row) >> 1) * (G * 4);
 #pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            consume_values<G>(ring[k % kRing], 4 * k, pw_row, rot_cur, acc);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              constexpr int kAhead = 4 * kRing;
-              const int nrow = 4 * k + r + kAhead;
-              if (nrow < 32)
-                ring[k % kRing][r] = buf_load16<kAuxStream>(rv_cur, voff_values, static_cast<uint32_t>((nrow + rot_cur) & 31) * 1024u);
-              else
-                ring[k % kRing][r] = buf_load16<kAuxStream>(rv_nxt, voff_values, static_cast<uint32_t>((nrow - 32 + rot_nxt) & 31) * 1024u);
+            for (int k = 0; k < kVLoads; ++k) {
+              consume_quantized<G, VB>(vq[k], pp + ((kTokPerLoad * k) >> 1) * (G * 4), acc);
+              vq[k] = buf_load16<kAuxStream>(rv_nxt, voff_values, k * 1024);
+              __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
+          } else {
+            const uint32_t pw_row = lds_addr(prob[pair][j & 1]) + row * (G * 4);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+              consume_values<G>(ring[k % kRing], 4 * k, pw_row, rot_cur, acc);
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                constexpr int kAhead = 4 * kRing;
+                const int nrow = 4 * k + r + kAhead;
+                if (nrow < 32)
+                  ring[k % kRing][r] = buf_load16<kAuxStream>(rv_cur, voff_values, static_cast<uint32_t>((nrow + rot_cur) & 31) * 1024u);
+                else
+                  ring[k % kRing][r] = buf_load16<kAuxStream>(rv_nxt, voff_values, static_cast<uint32_t>((nrow - 32 + rot_nxt) & 31) * 1024u);
+              }
+              __builtin_amdgcn_sched_barrier(0);
+            }
           }
           rv_cur = rv_nxt;
           rot_cur = rot_nxt;
@@ -316,7 +378,10 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
       for (int h = 0; h < G; ++h) {
         float tt[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) tt[e] = sum_rows(acc[h][e]);
+        for (int e = 0; e < 8; ++e) {
+          tt[e] = sum_rows(acc[h][e]);
+          if constexpr (kQuantV) tt[e] *= vq_unscale<VB>(e);
+        }
         if (row == 0) {
           float4* dst = reinterpret_cast<float4*>(&red_acc[pair][h][col * 8]);
           dst[0] = make_float4(tt[0], tt[1], tt[2], tt[3]);
@@ -336,10 +401,11 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
         for (int w = 0; w < kPairsOfWaves; ++w) {
           const float wgt = __builtin_amdgcn_exp2f(red_ml[w][h][0] - M);
           const f32x4 v = *reinterpret_cast<const f32x4*>(&red_acc[w][h][quad * 4]);
-          o.x = fmaf(wgt, v.x, o.x);
-          o.y = fmaf(wgt, v.y, o.y);
-          o.z = fmaf(wgt, v.z, o.z);
-          o.w = fmaf(wgt, v.w, o.w);
+          const float zp = red_ml[w][h][2];                              // zero-point term: the same for every dim
+          o.x = fmaf(wgt, v.x + zp, o.x);
+          o.y = fmaf(wgt, v.y + zp, o.y);
+          o.z = fmaf(wgt, v.z + zp, o.z);
+          o.w = fmaf(wgt, v.w + zp, o.w);
           l = fmaf(wgt, red_ml[w][h][1], l);
         }
       }

@@ -388,6 +388,10 @@ extern "C" int pq_encode_keys(const pq_layout* layout, const void* keys, pq_dtyp
   switch (layout->r_bits * 10 + layout->t_bits + (layout->angle_quantizer == PQ_ANGLE_GROUPED ? 100 : 0)) {
     case 144: e = launch_encode<4, 4, true>(a, key_dtype, grid, st); break;
     case 133: e = launch_encode<3, 3, true>(a, key_dtype, grid, st); break;
+    case 153: e = launch_encode<5, 3, true>(a, key_dtype, grid, st); break;
+    case 135: e = launch_encode<3, 5, true>(a, key_dtype, grid, st); break;
+    case 142: e = launch_encode<4, 2, true>(a, key_dtype, grid, st); break;
+    case 124: e = launch_encode<2, 4, true>(a, key_dtype, grid, st); break;
     case 44: e = launch_encode<4, 4>(a, key_dtype, grid, st); break;
     case 33: e = launch_encode<3, 3>(a, key_dtype, grid, st); break;
     case 53: e = launch_encode<5, 3>(a, key_dtype, grid, st); break;
@@ -444,6 +448,10 @@ extern "C" int pq_append_keys(const pq_layout* layout, const void* new_keys, pq_
   switch (layout->r_bits * 10 + layout->t_bits + (layout->angle_quantizer == PQ_ANGLE_GROUPED ? 100 : 0)) {
     case 144: e = launch_append<4, 4, true>(a, key_dtype, grid, st); break;
     case 133: e = launch_append<3, 3, true>(a, key_dtype, grid, st); break;
+    case 153: e = launch_append<5, 3, true>(a, key_dtype, grid, st); break;
+    case 135: e = launch_append<3, 5, true>(a, key_dtype, grid, st); break;
+    case 142: e = launch_append<4, 2, true>(a, key_dtype, grid, st); break;
+    case 124: e = launch_append<2, 4, true>(a, key_dtype, grid, st); break;
     case 44: e = launch_append<4, 4>(a, key_dtype, grid, st); break;
     case 33: e = launch_append<3, 3>(a, key_dtype, grid, st); break;
     case 53: e = launch_append<5, 3>(a, key_dtype, grid, st); break;

@@ -48,7 +48,7 @@ def test_page_sizes_and_bit_accounting(lib):
     assert pq.pq_codes_bytes_per_page(grouped) == pq.pq_codes_bytes_per_page(lay)
     assert 8 * (pq.pq_codes_bytes_per_page(grouped) + pq.pq_params_bytes_per_page(grouped)) / (8 * 128 * 128) == 4.25
     assert pq.pq_params_bytes_per_page(pq.Layout(128, 3, 3, 128, 8, 1)) == 2 * 8 * 64 * 4
-    assert pq.pq_params_bytes_per_page(pq.Layout(128, 5, 3, 128, 8, 1)) == 0     # grouped: (4,4), (3,3) only
+    assert pq.pq_params_bytes_per_page(pq.Layout(128, 5, 3, 128, 8, 1)) == 2 * 8 * 64 * 4     # any bit allocation
     assert pq.pq_params_bytes_per_page(pq.Layout(128, 4, 4, 128, 8, 2)) == 0     # unknown quantizer
     lay33 = pq.Layout(128, 3, 3, 128, 8)
     assert pq.pq_codes_bytes_per_page(lay33) == 8 * 128 * 48
@@ -109,9 +109,9 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert st == -1
     st = lib.pq_append_keys(ctypes.byref(lay), null, 0, 4, null, null, null, 8, null, null, 16, null)
     assert st == -1
-    # grouped angles exist for (4,4) and (3,3) only
-    grouped = pq.Layout(128, 5, 3, 128, 8, 1)
-    st = lib.pq_decode_partials(ctypes.byref(grouped), fake, 0, 1, 32, fake, fake, fake, 16, null, 4, fake, 1, fake, 128,
+    # r + t must be 6 or 8, with either angle quantizer
+    odd = pq.Layout(128, 5, 4, 128, 8, 1)
+    st = lib.pq_decode_partials(ctypes.byref(odd), fake, 0, 1, 32, fake, fake, fake, 16, null, 4, fake, 1, fake, 128,
                                 0.1, null, 0, null, fake, 1 << 20, null)
     assert st == -2
     # the allocation-free variant refuses, on the host, shapes beyond its static scratch array

@@ -54,6 +54,15 @@ SMALL = {
                                                      grouped_angles=True), np.array([0, 1, 128, 129, 300], np.int32)),
     "grouped_angles_ragged_pages": (WL["ragged"].scaled(n_seqs=6, n_q_heads=8, n_kv_heads=2, max_len=2000, min_len=1,
                                                         grouped_angles=True), None),
+    # ... with the bit allocations of the paper's ablation (Section 6.1)
+    "grouped_angles_r5t3": (WL["gqa"].scaled(n_seqs=2, n_q_heads=8, n_kv_heads=2, max_len=700, min_len=700, r_bits=5, t_bits=3,
+                                             grouped_angles=True), None),
+    "grouped_angles_r3t5": (WL["gqa"].scaled(n_seqs=2, n_q_heads=4, n_kv_heads=2, max_len=700, min_len=700, r_bits=3, t_bits=5,
+                                             grouped_angles=True), None),
+    "grouped_angles_r4t2": (WL["mha"].scaled(n_seqs=2, n_q_heads=2, n_kv_heads=2, max_len=700, min_len=700, r_bits=4, t_bits=2,
+                                             grouped_angles=True), None),
+    "grouped_angles_r2t4": (WL["gqa"].scaled(n_seqs=2, n_q_heads=12, n_kv_heads=2, max_len=700, min_len=700, r_bits=2, t_bits=4,
+                                             grouped_angles=True, key_dtype="f32"), None),
 }
 
 
@@ -219,7 +228,7 @@ def test_results_are_deterministic():
 
 @pytest.mark.parametrize("name", ["gqa_ragged_tail", "tiny33_fp32", "group_of_two", "ragged_pages", "bits_r5t3",
                                   "group_of_six", "grouped_angles_gqa", "grouped_angles_edge_lengths",
-                                  "grouped_angles_r3t3_many_chunks"])
+                                  "grouped_angles_r3t3_many_chunks", "grouped_angles_r3t5", "grouped_angles_r4t2"])
 def test_score_keys_entry_point(name):
     """pq_score_keys (the query-key product alone) against the oracle's dequantize-then-dot scores,
     and against the scores pq_decode_attention reports for the same cache."""
@@ -252,7 +261,10 @@ def test_score_keys_entry_point(name):
 @pytest.mark.parametrize("case", [("gqa_ragged_tail", 4), ("gqa_ragged_tail", 2), ("tiny_full_config", 4),
                                   ("long33", 2), ("group_of_two", 4), ("edge_lengths", 4), ("ragged_pages", 2),
                                   ("group_of_seven", 4), ("grouped_angles_gqa", 4), ("grouped_angles_r3t3_many_chunks", 2),
-                                  ("grouped_angles_edge_lengths", 2)])
+                                  ("grouped_angles_edge_lengths", 2), ("bits_r5t3", 4), ("bits_r3t5", 2), ("bits_r4t2", 4),
+                                  ("bits_r2t4", 2), ("grouped_angles_r5t3", 2), ("grouped_angles_r2t4", 4),
+                                  ("big_r5t3_g1", 4), ("big_r2t4_g2", 2), ("big_r4t4_g4", 4), ("big_r3t5_g2", 4),
+                                  ("big_fp32_r3t3_g2", 2), ("big_ragged_r3t3", 4), ("mha_two_seqs", 2)])
 def test_quantized_values(case):
     """Token-wise 4/2-bit values: pq_encode_values bit-exact against the oracle's quantizer and
     packer; decode attention over them within the output bar of the oracle's attention over the
@@ -261,7 +273,8 @@ def test_quantized_values(case):
     from paper_2502_00527_amd.cache import build_device_cache
 
     name, v_bits = case
-    wl, lens = SMALL[name]
+    wl, lens = SMALL[name] if name in SMALL else LARGE_GRID[name]
+    lens = _lengths(wl, lens)
     cache = build_device_cache(wl, lens=lens, v_bits=v_bits)
     _say(f"[parity] quantized values {name} v{v_bits}: decode launch")
     out = cache.decode().cpu().numpy()
@@ -467,7 +480,7 @@ def test_random_shapes():
         n_kv = int(rng.choice([1, 2, 3, 5]))
         group = int(rng.choice([1, 2, 3, 4, 5, 8, 9, 16]))
         grouped = bool(rng.random() < 0.4)
-        r, t = (4, 4) if grouped and rng.random() < 0.5 else ((3, 3) if grouped else bit_choices[int(rng.integers(6))])
+        r, t = bit_choices[int(rng.integers(6))]
         n_seqs = int(rng.integers(1, 7))
         max_len = int(rng.integers(1, 1400))
         base = WL["ragged"] if rng.random() < 0.5 else WL["mha"]
