@@ -127,7 +127,7 @@ constexpr int kComputeUnits = 256;           // MI355X
 #define PQ_BALANCED_MIN_PAGES 4
 #endif
 #ifndef PQ_BALANCED_GROUPS
-#define PQ_BALANCED_GROUPS (kComputeUnits * kRoleGroupsPerCu)
+#define PQ_BALANCED_GROUPS (kComputeUnits * role_groups_per_cu(4))
 #endif
 constexpr int kBalancedMinPages = PQ_BALANCED_MIN_PAGES;   // smallest share of a work-group: two pages per wavefront pair
 #ifndef PQ_BALANCED_UNIT_COST
@@ -138,11 +138,11 @@ constexpr int kBalancedMaxSeqs = 4096;       // every work-group scans all seque
 
 // Work-groups of a balanced launch: all that are resident at once (3 per compute unit), fewer if
 // the shape cannot have kBalancedMinPages pages for each.
-int balanced_groups(const pq_layout* l, int32_t n_seqs, int32_t max_seq_len) {
+int balanced_groups(const pq_layout* l, int32_t n_seqs, int32_t max_seq_len, int per_cu = role_groups_per_cu(4)) {
   const int64_t max_pages = (static_cast<int64_t>(max_seq_len) + kGroup - 1) / kGroup;
   const int64_t bound = static_cast<int64_t>(n_seqs) * l->n_kv_heads * max_pages;   // pages x KV heads, at most
-  return static_cast<int>(std::min<int64_t>(PQ_BALANCED_GROUPS,
-                                            (bound + kBalancedMinPages - 1) / kBalancedMinPages));
+  const int64_t resident = std::min<int64_t>(PQ_BALANCED_GROUPS, static_cast<int64_t>(kComputeUnits) * per_cu);
+  return static_cast<int>(std::min<int64_t>(resident, (bound + kBalancedMinPages - 1) / kBalancedMinPages));
 }
 
 AttentionKernel choose_attention_kernel(const pq_layout* l, int32_t v_bits, int32_t n_seqs, int32_t n_q_heads,
@@ -329,16 +329,17 @@ int decode_launch(const pq_layout* layout, const void* q, pq_dtype q_dtype, int3
 #endif
   const dim3 grid(layout->n_kv_heads, n_seqs, plan.n_chunks);
   hipError_t e = hipSuccess;
-  // A kernel instance serves 4, 2 or 1 query heads of a KV head; larger or odd groups take
-  // several passes over the cache (6 = 4 + 2, 8 = 4 + 4, ...).
+  // A kernel instance serves 8, 4, 2 or 1 query heads of a KV head; other groups take several
+  // passes over the cache (6 = 4 + 2, 12 = 8 + 4, ...).
   for (int head0 = 0; head0 < group_total && e == hipSuccess;) {
     const int left = group_total - head0;
-    const int G = left >= 4 ? 4 : (left >= 2 ? 2 : 1);
+    // 8 heads at a time where there is a kernel for it: the role-specialised one, fp16 values
+    const int G = (left >= 8 && roles && v_bits == 16) ? 8 : (left >= 4 ? 4 : (left >= 2 ? 2 : 1));
     a.head0 = head0;
     bool found;
     if (roles) {
       found = a.grid_mode ? launch_attention_roles_grid(rt, G, v_bits, a, static_cast<int>(grid.x * grid.y * grid.z), stream)
-                          : launch_attention_roles(rt, G, v_bits, a, n_balanced, stream);
+                          : launch_attention_roles(rt, G, v_bits, a, std::min(n_balanced, balanced_groups(layout, n_seqs, max_seq_len, role_groups_per_cu(G))), stream);
     } else {
       found = grouped ? launch_attention_partials_ga(rt, G, v_bits, a, grid, stream)
                       : launch_attention_partials(rt, G, v_bits, a, grid, stream);

@@ -120,17 +120,27 @@ __device__ __forceinline__ float row_sum(float x) {
   return x + __shfl_xor(x, 1);
 }
 // Sum of the four 16-lane rows' partial scores: with 4 query heads row h ends with head h's
-// score (transposing fold), with 2 heads rows 0-1 / 2-3, with 1 head every row.
+// score (transposing fold), with 2 heads rows 0-1 / 2-3, with 1 head every row; with 8 heads row h
+// ends with the scores of heads h and h + 4 (two transposing folds).
 template <int G>
-__device__ __forceinline__ float fold_rows(const float (&part)[G]) {
-  if constexpr (G == 4) {
-    return tsum16(tsum32(part[0], part[2]), tsum32(part[1], part[3]));
+struct Folded {
+  float v[G == 8 ? 2 : 1];
+};
+template <int G>
+__device__ __forceinline__ Folded<G> fold_rows(const float (&part)[G]) {
+  Folded<G> f;
+  if constexpr (G == 8) {
+    f.v[0] = tsum16(tsum32(part[0], part[2]), tsum32(part[1], part[3]));
+    f.v[1] = tsum16(tsum32(part[4], part[6]), tsum32(part[5], part[7]));
+  } else if constexpr (G == 4) {
+    f.v[0] = tsum16(tsum32(part[0], part[2]), tsum32(part[1], part[3]));
   } else if constexpr (G == 2) {
     const float b = tsum32(part[0], part[1]);
-    return tsum16(b, b);
+    f.v[0] = tsum16(b, b);
   } else {
-    return sum_rows(part[0]);
+    f.v[0] = sum_rows(part[0]);
   }
+  return f;
 }
 
 // LDS written by some lanes of this wavefront is about to be read by others.
@@ -224,10 +234,18 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((const PQ_LDS uint8_t*)p));
 }
 
-template <int G>
+// The G heads' values of one 16-byte entry; 8 heads are kept as two tables of 4-head entries, the
+// second one HALF bytes after the first, so that an entry's offset is the same in both.
+template <int G, int HALF = 0>
 __device__ __forceinline__ Heads<G> lut_read(uint32_t addr) {
   Heads<G> t;
-  if constexpr (G == 4) {
+  if constexpr (G == 8) {
+    static_assert(HALF > 0, "distance of the second table");
+    const f32x4 f = *(const PQ_LDS f32x4*)static_cast<uintptr_t>(addr);
+    const f32x4 g = *(const PQ_LDS f32x4*)static_cast<uintptr_t>(addr + HALF);
+    t.v[0] = f.x; t.v[1] = f.y; t.v[2] = f.z; t.v[3] = f.w;
+    t.v[4] = g.x; t.v[5] = g.y; t.v[6] = g.z; t.v[7] = g.w;
+  } else if constexpr (G == 4) {
     const f32x4 f = *(const PQ_LDS f32x4*)static_cast<uintptr_t>(addr);
     t.v[0] = f.x; t.v[1] = f.y; t.v[2] = f.z; t.v[3] = f.w;
   } else if constexpr (G == 2) {
@@ -300,7 +318,7 @@ __device__ __forceinline__ void score_steps(const Unit<(RB + TB) / 2>& u, uint32
       c = byte_to_float<0>(cq);
     }
     const float rho = fmaf(c, sf[K], zz[K]);
-    const Heads<G> t = lut_read<G>(addr + K * ROW);
+    const Heads<G> t = lut_read<G, kPairs * ROW>(addr + K * ROW);
 #pragma unroll
     for (int h = 0; h < G; ++h) part[h] = fmaf(rho, t.v[h], part[h]);
     score_steps<G, RB, TB, K + 1>(u, lut_row0, sf, zz, part);
@@ -325,8 +343,8 @@ __device__ __forceinline__ void dense_steps(const uint4 (&kx)[2], const uint4 (&
         const __half2 hv = *reinterpret_cast<const __half2*>(&w4[e]);
         const float k0 = __low2float(hv), k1 = __high2float(hv);
         const int dim = half * kPairs + v * 8 + 2 * e;            // relative to 16 * row
-        const Heads<G> q0 = lut_read<G>(qs_row + dim * 16);
-        const Heads<G> q1 = lut_read<G>(qs_row + (dim + 1) * 16);
+        const Heads<G> q0 = lut_read<G, kHeadDim * 16>(qs_row + dim * 16);
+        const Heads<G> q1 = lut_read<G, kHeadDim * 16>(qs_row + (dim + 1) * 16);
 #pragma unroll
         for (int h = 0; h < G; ++h) part[h] = fmaf(k1, q1.v[h], fmaf(k0, q0.v[h], part[h]));
       }
@@ -396,6 +414,45 @@ __device__ __forceinline__ uint32_t pack_with_neighbour(float x) {
       __builtin_amdgcn_update_dpp(0, static_cast<int>(f2u(x)), 0xB1 /* quad_perm(1,0,3,2) */, 0xf, 0xf, true)));
   const __half2 h = __floats2half2_rn(x, other);
   return *reinterpret_cast<const uint32_t*>(&h);
+}
+
+// The same with the lane four further on in its row of 16 (lane + 4): called where the lanes col
+// and col + 4 hold the probabilities of tokens n and n + 4; the lanes with (col & 4) == 0 store.
+__device__ __forceinline__ uint32_t pack_with_lane4(float x) {
+  const float other = u2f(static_cast<uint32_t>(
+      __builtin_amdgcn_update_dpp(0, static_cast<int>(f2u(x)), 0x104 /* row_shl:4 */, 0xf, 0xf, true)));
+  const __half2 h = __floats2half2_rn(x, other);
+  return *reinterpret_cast<const uint32_t*>(&h);
+}
+
+// fp16 values with 8 query heads: acc[h][0..7] += p_h[token] * V[token][this lane's 8 dims] for the
+// 4 value rows in `vv`, the (it0 + i)-th 1 KB loads of the page in its rotated order (rot even),
+// i.e. tokens 4 * ((it0 + i + rot) % 32) + row.  Rows i = 0, 1 and i = 2, 3 are token pairs
+// (n, n + 4): their values are interleaved dim by dim (v_perm_b32) into fp16 pairs and meet the
+// probability pairs [pair 4 * (load / 2) + row][8 heads] at `prob` in one v_dot2_f32_f16 per
+// head and dim -- half the instructions of one multiply-add per token.
+__device__ __forceinline__ void consume_values_pairs(const uint4 (&vv)[4], int it0, uint32_t prob, int rot, int row,
+                                                     float (&acc)[8][8]) {
+#pragma unroll
+  for (int i = 0; i < 4; i += 2) {
+    const uint32_t load = static_cast<uint32_t>((it0 + i + rot) & 31);
+    const uint32_t pa = prob + ((4u * (load >> 1) + static_cast<uint32_t>(row)) * 8u) * 4u;
+    const Pairs<4> p0 = pairs_read<4>(pa), p1 = pairs_read<4>(pa + 16);
+    const uint32_t wa[4] = {vv[i].x, vv[i].y, vv[i].z, vv[i].w};
+    const uint32_t wb[4] = {vv[i + 1].x, vv[i + 1].y, vv[i + 1].z, vv[i + 1].w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t lo = __builtin_amdgcn_perm(wb[e], wa[e], 0x05040100u);   // dim 2e of tokens n, n + 4
+      const uint32_t hi = __builtin_amdgcn_perm(wb[e], wa[e], 0x07060302u);   // dim 2e + 1
+#pragma unroll
+      for (int h = 0; h < 4; ++h) {
+        acc[h][2 * e] = dot2(p0.v[h], lo, acc[h][2 * e]);
+        acc[h][2 * e + 1] = dot2(p0.v[h], hi, acc[h][2 * e + 1]);
+        acc[h + 4][2 * e] = dot2(p1.v[h], lo, acc[h + 4][2 * e]);
+        acc[h + 4][2 * e + 1] = dot2(p1.v[h], hi, acc[h + 4][2 * e + 1]);
+      }
+    }
+  }
 }
 
 // Power of two an accumulator of dim k (of the lane's 8) is multiplied with at the end: undoes
@@ -468,8 +525,9 @@ __device__ __forceinline__ QueryRegs<G> fetch_query(const QT* qb, const DecodeAr
 template <int G>
 __device__ __forceinline__ void store_query_lds(float (*q_lds)[4], float2* trig, const QueryRegs<G>& r, int tid) {
   if (tid < kHeadDim) {
+    // heads 4-7 (G = 8) make a second [dim][4] table behind the first
 #pragma unroll
-    for (int h = 0; h < 4; ++h) q_lds[tid][h] = h < G ? r.q[h < G ? h : 0] : 0.f;
+    for (int h = 0; h < (G == 8 ? 8 : 4); ++h) q_lds[(h >> 2) * kHeadDim + tid][h & 3] = h < G ? r.q[h < G ? h : 0] : 0.f;
   } else if (tid < kHeadDim + kMaxAngleBins) {
     trig[tid - kHeadDim] = r.cs;
   }
@@ -529,7 +587,7 @@ __device__ __forceinline__ void unpack_radius_params(const uint4 (&praw)[4], flo
 // group): plain dot products in the score-phase lane layout (lane = (pair block row, token col),
 // each lane takes the 32 dims of its 16 pairs), folded like the table-lookup partial sums.  Key
 // rows past `nv_res` read as zero.  `emit(pass, score)` is called once per pass of 16 tokens with
-// the score of token 16 * pass + col for the lane's head (valid in the lanes that own a head).
+// the score(s) of token 16 * pass + col for the lane's head(s) (valid in the lanes that own a head).
 template <int G, typename Emit>
 __device__ __forceinline__ void residual_scores(const __half* res_rows, int nv_res, uint32_t q_lds_addr, int row,
                                                 int col, Emit emit) {
@@ -548,7 +606,7 @@ __device__ __forceinline__ void residual_scores(const __half* res_rows, int nv_r
 #pragma unroll
     for (int h = 0; h < G; ++h) part[h] = 0.f;
     dense_steps<G>(kx, ky, qs_row, part);
-    emit(s, fold_rows<G>(part));
+    emit(s, fold_rows<G>(part));   // a Folded<G>
   }
 }
 
@@ -748,8 +806,8 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   // the sequence end read as zero.  The loop below picks the scores up from LDS.
   if (res_page >= page0 + wave && res_page < page0 + npg && ((res_page - page0 - wave) & (kWaves - 1)) == 0) {
     residual_scores<G>(a.residual + (static_cast<int64_t>(seq) * a.n_kv_heads + kvh) * (kGroup * kHeadDim),
-                       L - res_page * kGroup, lds_addr(q_lds), row, col, [&](int s, float v) {
-                         if (owner) res_sc[(s * 16 + col) * G + my_head] = v;
+                       L - res_page * kGroup, lds_addr(q_lds), row, col, [&](int s, Folded<G> v) {
+                         if (owner) res_sc[(s * 16 + col) * G + my_head] = v.v[0];
                        });
     wave_lds_sync();
   }
@@ -783,7 +841,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
 #pragma unroll
         for (int h = 0; h < G; ++h) part[h] = 0.f;
         score_steps<G, RB, TB, 0>(cu[s], lut_row0, sf, zz, part);
-        sc[s] = fold_rows<G>(part);
+        sc[s] = fold_rows<G>(part).v[0];
       }
     } else {
       // residual group: its scores were computed before the loop (plain dot products)
@@ -1010,9 +1068,9 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
   if (res_page >= page0 + wave && res_page < page0 + npg && ((res_page - page0 - wave) & (kWaves - 1)) == 0) {
     const int nv_res = L - res_page * kGroup;
     residual_scores<G>(a.residual + (static_cast<int64_t>(seq) * a.n_kv_heads + kvh) * (kGroup * kHeadDim), nv_res,
-                       lds_addr(q_lds), row, col, [&](int s, float v) {
+                       lds_addr(q_lds), row, col, [&](int s, Folded<G> v) {
                          const int tok = s * 16 + col;
-                         if (owner && tok < nv_res) out_row[static_cast<int64_t>(res_page) * kGroup + tok] = v;
+                         if (owner && tok < nv_res) out_row[static_cast<int64_t>(res_page) * kGroup + tok] = v.v[0];
                        });
   }
 
@@ -1041,7 +1099,7 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
       for (int h = 0; h < G; ++h) part[h] = 0.f;
       score_steps<G, RB, TB, 0>(cu[s], lut_row0, sf, zz, part);
       cu[s] = load_unit<W>(rc_nxt, voff_codes, s * 16 * UB);       // next page's pass s
-      const float sc = fold_rows<G>(part);
+      const float sc = fold_rows<G>(part).v[0];
       const int tok = s * 16 + col;
       if (owner && tok < nv_cur && pi != res_page) out_row[static_cast<int64_t>(pi) * kGroup + tok] = sc;
     }

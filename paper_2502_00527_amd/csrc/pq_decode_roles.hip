@@ -18,6 +18,12 @@ bool launch_g(int G, const DecodeArgs& a, int n_wg, hipStream_t st) {
     case 1: hipLaunchKernelGGL((pq_decode_roles_kernel<1, RB, TB, VB, PQ_ROLES_BALANCED>), grid, block, 0, st, a); return true;
     case 2: hipLaunchKernelGGL((pq_decode_roles_kernel<2, RB, TB, VB, PQ_ROLES_BALANCED>), grid, block, 0, st, a); return true;
     case 4: hipLaunchKernelGGL((pq_decode_roles_kernel<4, RB, TB, VB, PQ_ROLES_BALANCED>), grid, block, 0, st, a); return true;
+    case 8:
+      if constexpr (VB == 16) {
+        hipLaunchKernelGGL((pq_decode_roles_kernel<8, RB, TB, VB, PQ_ROLES_BALANCED>), grid, block, 0, st, a);
+        return true;
+      }
+      return false;
     default: return false;
   }
 }

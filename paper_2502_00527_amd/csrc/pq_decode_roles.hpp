@@ -34,7 +34,8 @@ namespace {
 
 constexpr int kPairsOfWaves = 2;                   // (score, value) wavefront pairs per work-group
 constexpr int kRoleThreads = kPairsOfWaves * 128;
-constexpr int kRoleGroupsPerCu = 3;                // resident work-groups per compute unit (3 wavefronts per SIMD)
+// Resident work-groups per compute unit = wavefronts per SIMD: 3 (168 registers each).
+constexpr int role_groups_per_cu(int) { return 3; }
 
 // Pool pages of the pages a wavefront pair handles in a segment (segment pages pair, pair + 2,
 // ...): lane k holds the id of the (base + k)-th of them, -1 for a block-table entry outside the
@@ -94,24 +95,36 @@ __device__ __forceinline__ void rotate_priority(int turn) {
 // are stored are run-time switches (a.q_is_f32, a.scores): both touch a few instructions per
 // page and are not worth kernels of their own.
 template <int G, int RB, int TB, int VB, bool BAL>
-__global__ __launch_bounds__(kRoleThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
+__global__ __launch_bounds__(kRoleThreads) __attribute__((amdgpu_waves_per_eu(role_groups_per_cu(G), role_groups_per_cu(G))))
 void pq_decode_roles_kernel(const DecodeArgs a) {
   constexpr int W = RB + TB;
   constexpr int UB = 2 * W;
   constexpr int NA = 1 << TB;
   constexpr int ROW = NA * 16;
-  constexpr int kRing = 4;                               // quads of 4 value rows in flight
+  constexpr int kRing = G == 8 ? 2 : 4;                  // quads of 4 value rows in flight (8 heads: registers for the accumulators)
   constexpr bool kQuantV = VB != 16;
+  // 8 query heads: two tables of 4-head entries; a lane of the score wavefront owns heads row and
+  // row + 4; probabilities go over as fp16 pairs (tokens n, n + 4) and the value wavefront uses
+  // the two-term dot product, which keeps its arithmetic at the level of 4 heads
+  constexpr int NH = G == 8 ? 2 : 1;
+  constexpr bool kPairP = kQuantV || G == 8;
+  static_assert(!(kQuantV && G == 8), "quantized values are served 4 heads at a time");
   constexpr int kVLoads = kQuantV ? kGroup * kHeadDim * VB / 8 / 1024 : 32;   // 1 KB wavefront loads per page of values
   constexpr int kTokPerLoad = kGroup / kVLoads;
 
-  __shared__ __attribute__((aligned(16))) uint8_t lut[kPairs * ROW];
-  // probabilities of a page: fp32 [token][G], or fp16 pairs [token pair][G] for quantized values
-  __shared__ __attribute__((aligned(16))) float prob[kPairsOfWaves][2][(kQuantV ? kGroup / 2 : kGroup) * G];
-  __shared__ __attribute__((aligned(16))) float alpha_s[kPairsOfWaves][2][4];
-  __shared__ __attribute__((aligned(16))) float red_acc[kPairsOfWaves][G][kHeadDim];
+  __shared__ __attribute__((aligned(16))) uint8_t lut[NH * kPairs * ROW];
+  // probabilities of a page: fp32 [token][G], or fp16 pairs [token pair][G] (quantized values, 8 heads)
+  __shared__ __attribute__((aligned(16))) float prob[kPairsOfWaves][2][(kPairP ? kGroup / 2 : kGroup) * G];
+  __shared__ __attribute__((aligned(16))) float alpha_s[kPairsOfWaves][2][G == 8 ? 8 : 4];
+  // With 8 heads the tables' memory (idle once the last page is scored, rebuilt for the next
+  // segment behind a barrier) also serves the end of the segment: the wavefronts' accumulators,
+  // then the combination of partials -- a third work-group per compute unit fits that way.
+  constexpr int kRedBytes = kPairsOfWaves * G * kHeadDim * 4;
+  constexpr bool kLendLut = G == 8 && NH * kPairs * ROW >= kRedBytes + finish_lds_floats(kRoleThreads) * 4;
+  __shared__ __attribute__((aligned(16))) float red_own[kLendLut ? 4 : kPairsOfWaves * G * kHeadDim];
+  float (*const red_acc)[G][kHeadDim] = reinterpret_cast<float (*)[G][kHeadDim]>(kLendLut ? reinterpret_cast<float*>(lut) : red_own);
   __shared__ float red_ml[kPairsOfWaves][G][3];                       // m, l, sum of p * zero-point
-  __shared__ __attribute__((aligned(16))) float q_lds[kHeadDim][4];
+  __shared__ __attribute__((aligned(16))) float q_lds[NH * kHeadDim][4];
   __shared__ float2 trig[kMaxAngleBins];
   __shared__ float res_sc[kGroup * G];
 
@@ -138,8 +151,8 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
     asm volatile("" : "+v"(tid));
     const int lane = tid & 63;
     const int row = lane >> 4, col = lane & 15;
-    const int my_head = (G == 4) ? row : (G == 2 ? (row >> 1) : 0);
-    const bool owner = (G == 4) || (G == 2 && (row & 1) == 0) || (G == 1 && row == 0);
+    const int my_head = (G >= 4) ? row : (G == 2 ? (row >> 1) : 0);   // with 8 heads also my_head + 4
+    const bool owner = (G >= 4) || (G == 2 && (row & 1) == 0) || (G == 1 && row == 0);
     const int seq = seg.seq, kvh = seg.kvh, page0 = seg.page0, npg = seg.npg, L = seg.L;
     // pages of this pair: segment pages pair, pair + 2, ...; the step count is the same for both pairs
     const int n_p = npg > pair ? (npg - pair + kPairsOfWaves - 1) / kPairsOfWaves : 0;
@@ -155,7 +168,12 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
       const uint32_t lut_row0 = lds_addr(lut) + row * (kPairsPerUnit * ROW);
       const uint32_t voff_codes = (row * kGroup + col) * UB;
       const uint32_t voff_params = row * (kPairsPerUnit * 4);
-      float m_run = kNegInf, l_run = 0.f, z_run = 0.f;
+      float m_run[NH], l_run[NH], z_run = 0.f;
+#pragma unroll
+      for (int i = 0; i < NH; ++i) {
+        m_run[i] = kNegInf;
+        l_run[i] = 0.f;
+      }
       const uint32_t voff_vpar = col * 4;
 
       // descriptors of the pair's k-th page: codes, radius parameters, value parameters (rvp: the
@@ -191,14 +209,17 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
 
       store_query_lds<G>(q_lds, trig, q_regs, tid);
       __syncthreads();
-      build_uniform_table<TB>(lut, q_lds, trig, tid, kRoleThreads);
+#pragma unroll
+      for (int i = 0; i < NH; ++i) build_uniform_table<TB>(lut + i * (kPairs * ROW), q_lds + i * kHeadDim, trig, tid, kRoleThreads);
       __syncthreads();
 
       // residual group (plain dot products), if this pair owns its page
       if (res_page >= page0 + pair && res_page < page0 + npg && ((res_page - page0 - pair) % kPairsOfWaves) == 0) {
         residual_scores<G>(a.residual + (static_cast<int64_t>(seq) * a.n_kv_heads + kvh) * (kGroup * kHeadDim),
-                           L - res_page * kGroup, lds_addr(q_lds), row, col, [&](int s, float v) {
-                             if (owner) res_sc[(s * 16 + col) * G + my_head] = v;
+                           L - res_page * kGroup, lds_addr(q_lds), row, col, [&](int s, Folded<G> v) {
+#pragma unroll
+                             for (int i = 0; i < NH; ++i)
+                               if (owner) res_sc[(s * 16 + col) * G + my_head + 4 * i] = v.v[i];
                            });
         wave_lds_sync();
       }
@@ -212,7 +233,7 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
           unpack_radius_params(praw, sf, zz);
 #pragma unroll
           for (int v4 = 0; v4 < 4; ++v4) praw[v4] = buf_load16<kAuxCached>(rp_nxt, voff_params, v4 * 16);
-          float sc[8];
+          float sc[NH][8];
 #pragma unroll
           for (int s = 0; s < 8; ++s) {
             float part[G];
@@ -220,66 +241,83 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
             for (int h = 0; h < G; ++h) part[h] = 0.f;
             score_steps<G, RB, TB, 0>(cu[s], lut_row0, sf, zz, part);
             cu[s] = load_unit<W>(rc_nxt, voff_codes, s * 16 * UB);       // the pair's next page, same pass
-            sc[s] = fold_rows<G>(part);
+            const Folded<G> f = fold_rows<G>(part);
+#pragma unroll
+            for (int i = 0; i < NH; ++i) sc[i][s] = f.v[i];
           }
           if (pi == res_page) {
 #pragma unroll
-            for (int s = 0; s < 8; ++s)
-              sc[s] = *(const PQ_LDS float*)static_cast<uintptr_t>(lds_addr(res_sc) + ((s * 16 + col) * G + my_head) * 4);
+            for (int i = 0; i < NH; ++i)
+#pragma unroll
+              for (int s = 0; s < 8; ++s)
+                sc[i][s] = *(const PQ_LDS float*)static_cast<uintptr_t>(lds_addr(res_sc) + ((s * 16 + col) * G + my_head + 4 * i) * 4);
           }
           // online softmax (log2 domain); probabilities and rescaling factor go to buffer t % 2
-          float pm = kNegInf;
-#pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            const int tok = k * 16 + col;
-            if (a.scores != nullptr) {
-              if (owner && tok < nv_cur)
-                a.scores[(static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0 + my_head) * a.scores_stride +
-                         static_cast<int64_t>(pi) * kGroup + tok] = sc[k];
-            }
-            sc[k] = (tok < nv_cur) ? sc[k] * a.scale_log2 : kNegInf;
-            pm = fmaxf(pm, sc[k]);
-          }
-          pm = row_max(pm);
-          const float m_new = fmaxf(m_run, pm);
-          const bool dead = !(m_new > kNegInf);
-          const float alpha = dead ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
           const uint32_t pw = lds_addr(prob[pair][t & 1]);
-          float psum = 0.f, zsum = 0.f;
 #pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            const float p = dead ? 0.f : __builtin_amdgcn_exp2f(sc[k] - m_new);
-            psum += p;
-            if constexpr (kQuantV) {
-              // V~ = code * s + z (Section 2): fold s into the probability, collect p * z; the
-              // probabilities of tokens 2m, 2m + 1 (neighbour lanes) go over as one fp16 pair
-              const __half2 sz = *reinterpret_cast<const __half2*>(&vpar[k]);
-              zsum = fmaf(p, __high2float(sz), zsum);
-              const uint32_t pr = pack_with_neighbour(p * __low2float(sz));
-              if (owner && (col & 1) == 0)
-                *(PQ_LDS uint32_t*)static_cast<uintptr_t>(pw + ((k * 8 + (col >> 1)) * G + my_head) * 4) = pr;
-            } else {
-              if (owner) *(PQ_LDS float*)static_cast<uintptr_t>(pw + ((k * 16 + col) * G + my_head) * 4) = p;
+          for (int i = 0; i < NH; ++i) {
+            const int head = my_head + 4 * i;
+            float pm = kNegInf;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+              const int tok = k * 16 + col;
+              if (a.scores != nullptr) {
+                if (owner && tok < nv_cur)
+                  a.scores[(static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0 + head) * a.scores_stride +
+                           static_cast<int64_t>(pi) * kGroup + tok] = sc[i][k];
+              }
+              sc[i][k] = (tok < nv_cur) ? sc[i][k] * a.scale_log2 : kNegInf;
+              pm = fmaxf(pm, sc[i][k]);
             }
+            pm = row_max(pm);
+            const float m_new = fmaxf(m_run[i], pm);
+            const bool dead = !(m_new > kNegInf);
+            const float alpha = dead ? 1.f : __builtin_amdgcn_exp2f(m_run[i] - m_new);
+            float psum = 0.f, zsum = 0.f;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+              const float p = dead ? 0.f : __builtin_amdgcn_exp2f(sc[i][k] - m_new);
+              psum += p;
+              if constexpr (kQuantV) {
+                // V~ = code * s + z (Section 2): fold s into the probability, collect p * z; the
+                // probabilities of tokens 2m, 2m + 1 (neighbour lanes) go over as one fp16 pair
+                const __half2 sz = *reinterpret_cast<const __half2*>(&vpar[k]);
+                zsum = fmaf(p, __high2float(sz), zsum);
+                const uint32_t pr = pack_with_neighbour(p * __low2float(sz));
+                if (owner && (col & 1) == 0)
+                  *(PQ_LDS uint32_t*)static_cast<uintptr_t>(pw + ((k * 8 + (col >> 1)) * G + head) * 4) = pr;
+              } else if constexpr (G == 8) {
+                // tokens n and n + 4 (lanes col, col + 4) as one fp16 pair: they are rows of two
+                // consecutive value loads of the same lane (pair index: 8 per pass of 16 tokens)
+                const uint32_t pr = pack_with_lane4(p);
+                if ((col & 4) == 0)
+                  *(PQ_LDS uint32_t*)static_cast<uintptr_t>(pw + ((k * 8 + (col & 3) + ((col >> 3) << 2)) * G + head) * 4) = pr;
+              } else {
+                if (owner) *(PQ_LDS float*)static_cast<uintptr_t>(pw + ((k * 16 + col) * G + head) * 4) = p;
+              }
+            }
+            if constexpr (kQuantV) z_run = fmaf(z_run, alpha, zsum);
+            l_run[i] = fmaf(l_run[i], alpha, psum);
+            m_run[i] = m_new;
+            if (owner && col == 0) alpha_s[pair][t & 1][head] = alpha;
           }
           if constexpr (kQuantV) {
-            z_run = fmaf(z_run, alpha, zsum);
 #pragma unroll
             for (int k = 0; k < 8; ++k) vpar[k] = buf_load4<kAuxCached>(rvp_nxt, voff_vpar, k * 64);
           }
-          l_run = fmaf(l_run, alpha, psum);
-          m_run = m_new;
-          if (owner && col == 0) alpha_s[pair][t & 1][my_head] = alpha;
           rc_cur = rc_nxt; rp_cur = rp_nxt; rvp_cur = rvp_nxt; nv_cur = nv_nxt;
         }
         __syncthreads();                                               // hand buffer t % 2 to the value wavefront
       }
-      const float l_tot = row_sum(l_run);
       const float z_tot = kQuantV ? row_sum(z_run) : 0.f;
-      if (owner && col == 0) {
-        red_ml[pair][my_head][0] = m_run;
-        red_ml[pair][my_head][1] = l_tot;
-        red_ml[pair][my_head][2] = z_tot;
+#pragma unroll
+      for (int i = 0; i < NH; ++i) {
+        const float l_tot = row_sum(l_run[i]);
+        if (owner && col == 0) {
+          red_ml[pair][my_head + 4 * i][0] = m_run[i];
+          red_ml[pair][my_head + 4 * i][1] = l_tot;
+          red_ml[pair][my_head + 4 * i][2] = z_tot;
+        }
       }
     } else {
       // =========================== VALUE wavefront ===========================
@@ -295,7 +333,7 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
         const bool ok = pid >= 0;
         const int64_t ph = ok ? static_cast<int64_t>(pid) * a.n_kv_heads + kvh : 0;
         const int nv = ok ? min(kGroup, L - (page0 + pair + kPairsOfWaves * k) * kGroup) : 0;
-        rot = ok ? (pid * 13 + kvh * 5) & 31 : 0;
+        rot = ok ? (pid * 13 + kvh * 5) & (G == 8 ? 30 : 31) : 0;   // even with 8 heads: loads 2m, 2m + 1 stay a token pair
         if constexpr (kQuantV) {
           // whole units are read; codes of slots past the sequence end are zero bytes and meet a
           // zero probability
@@ -323,7 +361,8 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
 
       store_query_lds<G>(q_lds, trig, q_regs, tid);
       __syncthreads();
-      build_uniform_table<TB>(lut, q_lds, trig, tid, kRoleThreads);
+#pragma unroll
+      for (int i = 0; i < NH; ++i) build_uniform_table<TB>(lut + i * (kPairs * ROW), q_lds + i * kHeadDim, trig, tid, kRoleThreads);
       __syncthreads();
 
       for (int t = 0; t < n_steps; ++t) {
@@ -332,12 +371,11 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
         if (j >= 0 && j < n_p) {
           page_setup(j + 1, rv_nxt, rot_nxt);
           {
-            const f32x4 al4 = *(const PQ_LDS f32x4*)static_cast<uintptr_t>(lds_addr(alpha_s[pair][j & 1]));
-            const float al[4] = {al4.x, al4.y, al4.z, al4.w};
+            const Heads<(G == 8 ? 8 : 4)> al = lut_read<(G == 8 ? 8 : 4), 16>(lds_addr(alpha_s[pair][j & 1]));
 #pragma unroll
             for (int h = 0; h < G; ++h)
 #pragma unroll
-              for (int e = 0; e < 8; ++e) acc[h][e] *= al[h];
+              for (int e = 0; e < 8; ++e) acc[h][e] *= al.v[h];
           }
           // all loads in flight have arrived before the page is taken up: the wavefront then issues its
           // refills in a burst, row after row of one page (measured 2 % faster than waking up for every row)
@@ -356,7 +394,8 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
             const uint32_t pw_row = lds_addr(prob[pair][j & 1]) + row * (G * 4);
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
-              consume_values<G>(ring[k % kRing], 4 * k, pw_row, rot_cur, acc);
+              if constexpr (G == 8) consume_values_pairs(ring[k % kRing], 4 * k, lds_addr(prob[pair][j & 1]), rot_cur, row, acc);
+              else consume_values<G>(ring[k % kRing], 4 * k, pw_row, rot_cur, acc);
 #pragma unroll
               for (int r = 0; r < 4; ++r) {
                 constexpr int kAhead = 4 * kRing;
@@ -392,7 +431,7 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
     __syncthreads();
 
     // ---- the two pairs' results become the segment's partial; finish (or merge) the unit ----
-    finish_segment<G, kRoleThreads, BAL>(a, seg, tid, [&](int h, int quad, float& M, float& l) {
+    finish_segment<G, kRoleThreads, BAL, kLendLut>(a, seg, tid, [&](int h, int quad, float& M, float& l) {
       M = fmaxf(red_ml[0][h][0], red_ml[1][h][0]);
       f32x4 o = {0.f, 0.f, 0.f, 0.f};
       l = 0.f;
@@ -410,7 +449,7 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
         }
       }
       return o;
-    });
+    }, kLendLut ? reinterpret_cast<float*>(lut + kRedBytes) : nullptr);
     if constexpr (BAL) more = next_segment(a, span, seg);
     else more = false;
   }

@@ -234,13 +234,17 @@ __device__ __forceinline__ void combine_partials(const DecodeArgs& a, int64_t fi
   float m = kNegInf;
   for (int k = j; k < count; k += TPH)
     m = fmaxf(m, u2f(__builtin_amdgcn_raw_buffer_load_b32(r_ml, k * stride * slot_ml + h * 8, 0, kAuxDevice)));
+  // maximum over the head's TPH threads: within the wavefront by shuffles, beyond it through LDS
 #pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d));
+  for (int d = (TPH < 64 ? TPH : 64) / 2; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d));
   if ((tid & 63) == 0) wave_max[tid >> 6] = m;
   __syncthreads();
-  M = kNegInf;
+  M = m;
+  if constexpr (TPH > 64) {
+    M = kNegInf;
 #pragma unroll
-  for (int w = 0; w < TPH / 64; ++w) M = fmaxf(M, wave_max[h * (TPH / 64) + w]);
+    for (int w = 0; w < TPH / 64; ++w) M = fmaxf(M, wave_max[h * (TPH / 64) + w]);
+  }
   f32x4 o = {0.f, 0.f, 0.f, 0.f};
   float l = 0.f;
   if (M > kNegInf) {
@@ -281,9 +285,19 @@ __device__ __forceinline__ void combine_partials(const DecodeArgs& a, int64_t fi
 // L2s) and ordered by waiting for the stores before the arrival is registered -- not by fences,
 // which write back and invalidate whole caches (measured: with fences in every work-group the
 // launch takes twice as long).
-template <int G, int NT, bool BAL, typename Partial>
-__device__ __forceinline__ void finish_segment(const DecodeArgs& a, const Segment& seg, int tid, Partial partial) {
-  static_assert(NT == 256 && (G == 1 || G == 2 || G == 4), "thread mapping of the merge");
+template <int G, int NT, bool OWN_LDS, typename Partial>
+__device__ __forceinline__ void finish_balanced(const DecodeArgs& a, const Segment& seg, int tid, Partial partial,
+                                                float* lent);
+
+// LDS the combination of partials needs (floats): NT 4-float accumulators, NT denominators, one
+// maximum per wavefront.  A kernel may lend memory that is idle at the end of a segment
+// (`lent`, 16-byte aligned); otherwise the function has arrays of its own.
+constexpr int finish_lds_floats(int NT) { return NT * 4 + NT + NT / 64; }
+
+template <int G, int NT, bool BAL, bool LENT = false, typename Partial>
+__device__ __forceinline__ void finish_segment(const DecodeArgs& a, const Segment& seg, int tid, Partial partial,
+                                               float* lent = nullptr) {
+  static_assert(NT == 256 && (G == 1 || G == 2 || G == 4 || G == 8), "thread mapping of the merge");
   if constexpr (!BAL) {
     // one work-group per (sequence, KV head, chunk): the partial goes to the chunk's slot and
     // pq_decode_merge_kernel, launched next, combines the chunks
@@ -300,17 +314,20 @@ __device__ __forceinline__ void finish_segment(const DecodeArgs& a, const Segmen
     }
     return;
   } else {
-    finish_balanced<G, NT>(a, seg, tid, partial);
+    finish_balanced<G, NT, !LENT>(a, seg, tid, partial, lent);
   }
 }
 
-template <int G, int NT, typename Partial>
-__device__ __forceinline__ void finish_balanced(const DecodeArgs& a, const Segment& seg, int tid, Partial partial) {
+template <int G, int NT, bool OWN_LDS, typename Partial>
+__device__ __forceinline__ void finish_balanced(const DecodeArgs& a, const Segment& seg, int tid, Partial partial,
+                                                float* lent) {
   constexpr int TPH = NT / G;            // threads per query head in the merge
   constexpr int kSlices = TPH / 32;      // each takes every kSlices-th segment; 32 threads x 4 dims per slice
-  __shared__ __attribute__((aligned(16))) f32x4 part_o[NT];
-  __shared__ float part_l[NT];
-  __shared__ float wave_max[NT / 64];
+  __shared__ __attribute__((aligned(16))) float own[OWN_LDS ? finish_lds_floats(NT) : 4];
+  float* const mem = OWN_LDS ? own : lent;
+  f32x4* const part_o = reinterpret_cast<f32x4*>(mem);
+  float* const part_l = mem + NT * 4;
+  float* const wave_max = mem + NT * 5;
   __shared__ int stage;                  // after an arrival: 0 not last, 1 last at the unit's word, 2 last of a block
 
   const int unit = seg.seq * a.n_kv_heads + seg.kvh;

@@ -30,7 +30,7 @@ def test_append_then_decode_with_residual(bits):
 
 
 @pytest.mark.parametrize("bits", [(4, 4, 4, "f16"), (3, 3, 2, "f16"), (5, 3, 1, "f16"), (2, 4, 4, "f32"),
-                                  (3, 5, 6, "f16"), (4, 2, 2, "f32")])
+                                  (3, 5, 6, "f16"), (4, 2, 2, "f32"), (4, 4, 8, "f16"), (3, 3, 8, "f32")])
 def test_append_then_decode_large_batch(bits):
     """The same run with 256 (sequence, KV head) units, which the role-specialised attention kernel
     serves: residual groups of every fill level at once (the start lengths differ by 5 tokens from

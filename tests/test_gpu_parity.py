@@ -87,6 +87,19 @@ LARGE_GRID = {
     "big_group_of_six": (WL["gqa"].scaled(n_q_heads=48, **_BIG), None),                           # 4 + 2
     "big_group_of_eight_r3t3": (WL["gqa"].scaled(n_q_heads=64, r_bits=3, t_bits=3, **_BIG), None),  # 4 + 4
     "big_group_of_seven_r4t2": (WL["gqa"].scaled(n_q_heads=56, r_bits=4, t_bits=2, **_BIG), None),  # 4 + 2 + 1
+    # 8 query heads per KV head are served in one pass (two tables, fp16 probability pairs)
+    "big_group_of_eight_r4t4": (WL["gqa"].scaled(n_q_heads=64, **_BIG), None),
+    "big_group_of_eight_r5t3_fp32": (WL["gqa"].scaled(n_q_heads=64, r_bits=5, t_bits=3, key_dtype="f32", **_BIG), None),
+    "big_group_of_eight_r3t5": (WL["mha"].scaled(n_q_heads=64, r_bits=3, t_bits=5, **_BIG), None),
+    "big_group_of_twelve_r4t2": (WL["gqa"].scaled(n_seqs=32, n_kv_heads=8, n_q_heads=96, max_len=520, min_len=520,
+                                                  r_bits=4, t_bits=2), None),                              # 8 + 4
+    "big_group_of_sixteen_r2t4": (WL["gqa"].scaled(n_seqs=32, n_kv_heads=8, n_q_heads=128, max_len=520, min_len=520,
+                                                   r_bits=2, t_bits=4), None),                             # 8 + 8
+    "big_ragged_group_of_eight": (WL["ragged"].scaled(n_seqs=48, n_q_heads=64, n_kv_heads=8, max_len=1500, min_len=1),
+                                  "ragged_with_zeros"),
+    # few (sequence, KV head) units, each cut into many chunks: one work-group per chunk + merge kernel
+    "few_units_group_of_eight": (WL["gqa"].scaled(n_seqs=1, n_q_heads=64, n_kv_heads=8, max_len=20011, min_len=20011), None),
+    "few_units_group_of_four_r3t3": (WL["long33"].scaled(n_seqs=2, n_q_heads=32, n_kv_heads=8, max_len=12000, min_len=12000), None),
     "big_ragged_with_empty": (WL["ragged"].scaled(n_seqs=48, n_q_heads=32, n_kv_heads=8, max_len=1500, min_len=1),
                               "ragged_with_zeros"),
     "big_ragged_r3t3": (WL["ragged"].scaled(n_seqs=40, n_q_heads=16, n_kv_heads=8, max_len=2100, min_len=1,
@@ -335,7 +348,8 @@ def test_block_table_entry_outside_pool_is_masked():
         assert np.abs(out[s] - want).max() <= OUT_ABS
 
 
-def test_masked_pages_in_a_large_grid():
+@pytest.mark.parametrize("n_q_heads", [32, 64])
+def test_masked_pages_in_a_large_grid(n_q_heads):
     """Block-table entries outside the pool (too large, negative) in a launch served by the
     role-specialised kernel: those pages count as masked, for either wavefront pair of a
     work-group and for first, middle and last pages of a chunk."""
@@ -343,7 +357,7 @@ def test_masked_pages_in_a_large_grid():
     from paper_2502_00527_amd import pq_decode_kernel_name
     from paper_2502_00527_amd.cache import build_device_cache
 
-    wl = WL["gqa"].scaled(n_seqs=32, n_q_heads=32, n_kv_heads=8, max_len=1100, min_len=1100)
+    wl = WL["gqa"].scaled(n_seqs=32, n_q_heads=n_q_heads, n_kv_heads=8, max_len=1100, min_len=1100)
     cache = build_device_cache(wl)
     assert pq_decode_kernel_name(cache.layout, wl.n_seqs, wl.n_q_heads, cache.max_seq_len) == "pq_decode_roles_kernel"
     # sequence 20 loses the whole of its first chunk (8 pages), sequence 21 every page
