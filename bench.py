@@ -126,9 +126,9 @@ def cpu_baseline(wl, lens, budget_s: float = 10.0):
 def read_traffic_note(workload: str, kernel: str):
     """(HBM bytes per launch, source) of the dominant kernel as measured with rocprofv3 --pmc, if a
     committed summary for this workload states it for the kernel that runs
-    (profiles/decode_partials_<workload>_pmc.txt); counters cannot be read inside a timed run, so
+    (profiles/decode_attention_<workload>_pmc.txt); counters cannot be read inside a timed run, so
     this is a recorded figure, not one measured by this process."""
-    rel = os.path.join("profiles", f"decode_partials_{workload}_pmc.txt")
+    rel = os.path.join("profiles", f"decode_attention_{workload}_pmc.txt")
     try:
         with open(os.path.join(ROOT, rel)) as f:
             text = f.read()
@@ -268,7 +268,7 @@ def main() -> int:
     # role-specialised kernel merges inside the kernel: the step IS that one kernel, timed again
     # here in a region of its own; the other kernels are followed by a separate merge kernel.
     kernel = pq.pq_decode_kernel_name(cache.layout, wl.n_seqs, wl.n_q_heads, cache.max_seq_len, args.v_bits)
-    one_kernel_step = kernel == "pq_decode_roles_kernel"
+    one_kernel_step = pq.pq_decode_merges_in_kernel(cache.layout, wl.n_seqs, wl.n_q_heads, cache.max_seq_len, args.v_bits)
     ms_partials = time_region(step if one_kernel_step else partials_only, args.steps, torch)
     ms_merge = 0.0 if one_kernel_step else time_region(merge_only, args.steps, torch)
     # what this device streams with bare non-temporal 128-bit loads (context for the roofline

@@ -266,6 +266,16 @@ const char* pq_decode_kernel_name(const pq_layout* layout, int32_t n_seqs, int32
                                   int32_t max_seq_len, int32_t v_bits);
 
 /*
+ * pq_decode_merges_in_kernel -- 1 if pq_decode_attention serves this shape with one kernel that
+ * shares the launch out evenly and combines the partial results itself, 0 if it launches one
+ * work-group per chunk followed by the merge kernel; a negative pq_status on invalid arguments.
+ * Launches of few (sequence, KV head) units and the kernels without role specialisation take the
+ * second form.  For profiles and the benchmark, like pq_decode_kernel_name.
+ */
+int pq_decode_merges_in_kernel(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
+                               int32_t max_seq_len, int32_t v_bits);
+
+/*
  * pq_append_keys -- one decode step's new key per sequence.  Methods of this kind keep the most
  * recent keys un-quantized until a full group exists (the "residual" of Appendix B.1): the key of
  * token len (len = seq_lens[s], the length BEFORE the append) is rounded to fp16 and stored in slot

@@ -23,7 +23,7 @@ __all__ = [
     "pq_values_bytes_per_page", "pq_decode_workspace_bytes", "pq_encode_keys",
     "pq_decode_attention", "pq_decode_partials", "pq_decode_merge", "pq_score_keys", "pq_append_keys",
     "pq_vq_bytes_per_page", "pq_vq_params_bytes_per_page", "pq_encode_values",
-    "pq_probe_read_stream", "pq_decode_kernel_name",
+    "pq_probe_read_stream", "pq_decode_kernel_name", "pq_decode_merges_in_kernel",
     "pq_decode_attention_static", "PQ_STATIC_SCRATCH_BYTES",
 ]
 
@@ -81,6 +81,7 @@ _SIGNATURES = {
     "pq_score_keys": (c_int, [_LP, c_void_p, c_int, c_int32, c_int32, c_void_p, c_void_p, c_int64, c_void_p,
                               c_int32, c_void_p, c_int32, c_void_p, c_int64, c_void_p, c_void_p]),
     "pq_decode_kernel_name": (ctypes.c_char_p, [_LP, c_int32, c_int32, c_int32, c_int32]),
+    "pq_decode_merges_in_kernel": (c_int32, [_LP, c_int32, c_int32, c_int32, c_int32]),
     "pq_probe_read_stream": (c_int, [c_void_p, c_size_t, c_void_p, c_void_p]),
 }
 
@@ -157,6 +158,13 @@ def pq_values_bytes_per_page(layout: Layout) -> int:
 
 def pq_decode_workspace_bytes(layout: Layout, n_seqs: int, n_q_heads: int, max_seq_len: int) -> int:
     return load_library().pq_decode_workspace_bytes(ctypes.byref(layout), n_seqs, n_q_heads, max_seq_len)
+
+
+def pq_decode_merges_in_kernel(layout: Layout, n_seqs: int, n_q_heads: int, max_seq_len: int, v_bits: int = 16) -> bool:
+    st = load_library().pq_decode_merges_in_kernel(ctypes.byref(layout), n_seqs, n_q_heads, max_seq_len, v_bits)
+    if st < 0:
+        _check(st, "pq_decode_merges_in_kernel")
+    return bool(st)
 
 
 def pq_decode_kernel_name(layout: Layout, n_seqs: int, n_q_heads: int, max_seq_len: int, v_bits: int = 16) -> str:

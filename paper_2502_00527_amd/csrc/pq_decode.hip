@@ -249,6 +249,17 @@ extern "C" size_t pq_decode_workspace_bytes(const pq_layout* layout, int32_t n_s
 namespace pq {
 namespace {
 
+// Whether pq_decode_attention shares this launch out evenly and merges inside the attention kernel
+// (true), or launches one work-group per chunk and the merge kernel after it.
+bool merges_in_kernel(const pq_layout* l, int32_t v_bits, int32_t n_seqs, int32_t n_q_heads, int32_t max_seq_len) {
+#ifdef PQ_FORCE_GRID
+  return false;
+#else
+  if (choose_attention_kernel(l, v_bits, n_seqs, n_q_heads, max_seq_len) != AttentionKernel::kRoles) return false;
+  return static_cast<int64_t>(n_seqs) * l->n_kv_heads * kArriveFan >= balanced_groups(l, n_seqs, max_seq_len);
+#endif
+}
+
 // Everything the decode entry points have in common: argument checks, kernel arguments, and the
 // launches.  `out` null = only the first stage of the two-stage (grid) path, the chunk partials.
 int decode_launch(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs, int32_t n_q_heads,
@@ -321,12 +332,8 @@ int decode_launch(const pq_layout* layout, const void* q, pq_dtype q_dtype, int3
   // chunk, and the merge kernel.
   const bool roles = choose_attention_kernel(layout, v_bits, n_seqs, n_q_heads, max_seq_len) == AttentionKernel::kRoles;
   const int n_balanced = balanced_groups(layout, n_seqs, max_seq_len);
-  const bool balanced = roles && out != nullptr && static_cast<int64_t>(n_seqs) * layout->n_kv_heads * kArriveFan >= n_balanced;
-#ifdef PQ_FORCE_GRID
-  a.grid_mode = 1;
-#else
+  const bool balanced = out != nullptr && merges_in_kernel(layout, v_bits, n_seqs, n_q_heads, max_seq_len);
   a.grid_mode = balanced ? 0 : 1;
-#endif
   const dim3 grid(layout->n_kv_heads, n_seqs, plan.n_chunks);
   hipError_t e = hipSuccess;
   // A kernel instance serves 8, 4, 2 or 1 query heads of a KV head; other groups take several
@@ -379,6 +386,13 @@ extern "C" const char* pq_decode_kernel_name(const pq_layout* layout, int32_t n_
   if (check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len) != PQ_OK) return "";
   return choose_attention_kernel(layout, v_bits, n_seqs, n_q_heads, max_seq_len) == AttentionKernel::kRoles
              ? "pq_decode_roles_kernel" : "pq_decode_partials_kernel";
+}
+
+extern "C" int pq_decode_merges_in_kernel(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,
+                                          int32_t max_seq_len, int32_t v_bits) {
+  const int st = check_decode_shape(layout, n_seqs, n_q_heads, max_seq_len);
+  if (st != PQ_OK) return st;
+  return merges_in_kernel(layout, v_bits, n_seqs, n_q_heads, max_seq_len) ? 1 : 0;
 }
 
 extern "C" int pq_decode_merge(const pq_layout* layout, int32_t n_seqs, int32_t n_q_heads,

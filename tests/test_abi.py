@@ -77,6 +77,26 @@ def test_workspace_size_follows_the_chunk_plan(lib):
     assert pq.pq_decode_workspace_bytes(lay, 64, 32, 65535 * 32 * 128) > 0
 
 
+def test_dispatch_queries(lib):
+    """Which kernel serves a shape, and whether it merges itself, are host decisions the library reports."""
+    lay = pq.Layout(128, 4, 4, 128, 8)
+    # the headline shape: role-specialised kernel, launch shared out evenly, merge in the kernel
+    assert pq.pq_decode_kernel_name(lay, 16, 32, 32768) == "pq_decode_roles_kernel"
+    assert pq.pq_decode_merges_in_kernel(lay, 16, 32, 32768) is True
+    # one long sequence: same kernel, but one work-group per chunk and the merge kernel
+    lay33 = pq.Layout(128, 3, 3, 128, 8)
+    assert pq.pq_decode_kernel_name(lay33, 1, 32, 131072) == "pq_decode_roles_kernel"
+    assert pq.pq_decode_merges_in_kernel(lay33, 1, 32, 131072) is False
+    # small launches and 4-bit values at four query heads per KV head: the alternating-phase kernel
+    assert pq.pq_decode_kernel_name(lay, 2, 32, 1024) == "pq_decode_partials_kernel"
+    assert pq.pq_decode_merges_in_kernel(lay, 2, 32, 1024) is False
+    assert pq.pq_decode_kernel_name(lay, 16, 32, 32768, 4) == "pq_decode_partials_kernel"
+    assert pq.pq_decode_kernel_name(lay, 16, 16, 32768, 4) == "pq_decode_roles_kernel"
+    assert pq.pq_decode_kernel_name(lay, 0, 32, 128) == ""
+    with pytest.raises(pq.PolarQuantError):
+        pq.pq_decode_merges_in_kernel(lay, 0, 32, 128)
+
+
 def test_argument_errors_are_reported_before_any_launch(lib):
     lay = pq.Layout(128, 4, 4, 128, 8)
     null = ctypes.c_void_p(0)
