@@ -300,7 +300,9 @@ int pq_append_keys(const pq_layout* layout, const void* new_keys, pq_dtype key_d
  * through the lookup table (Section 3.3, Appendix A).  This is the operation whose latency
  * the paper reports in Section 5.2 (query-key multiplication kernel).  Arguments as in
  * pq_decode_attention; `scores` (device fp32 [n_seqs][n_q_heads][scores_stride], scores_stride
- * >= max_seq_len) receives the scores of tokens < seq_len, other elements are left untouched.
+ * >= max_seq_len, < 2^28: PQ_ERR_UNSUPPORTED beyond) receives the scores of tokens < seq_len,
+ * other elements are left untouched.  A score equals, bit for bit, the one pq_decode_attention
+ * computes (and reports through its own `scores` argument) for the same cache and query.
  * No workspace is needed.  residual_keys as in pq_decode_attention (NULL: every group is read
  * from the packed pages).
  */

@@ -89,13 +89,19 @@ __global__ __launch_bounds__(kMergeThreads) void pq_decode_merge_kernel(
   }
 }
 
+// Score-only kernels: uniform angle grid -> lanes are tokens (pq_score_tokens_kernel); grouped
+// quantizer -> the attention kernels' lane layout with a table per page (pq_score_keys_kernel).
+template <int G, int RB, int TB, bool GA>
+void launch_scores_one(const DecodeArgs& a, dim3 grid, hipStream_t st) {
+  if constexpr (GA) hipLaunchKernelGGL((pq_score_keys_kernel<G, RB, TB, true>), grid, dim3(kThreads), 0, st, a);
+  else hipLaunchKernelGGL((pq_score_tokens_kernel<G, RB, TB>), grid, dim3(kThreads), 0, st, a);
+}
 template <int RB, int TB, bool GA>
 bool launch_scores_g(int G, const DecodeArgs& a, dim3 grid, hipStream_t st) {
-  const dim3 block(kThreads);
   switch (G) {
-    case 1: hipLaunchKernelGGL((pq_score_keys_kernel<1, RB, TB, GA>), grid, block, 0, st, a); return true;
-    case 2: hipLaunchKernelGGL((pq_score_keys_kernel<2, RB, TB, GA>), grid, block, 0, st, a); return true;
-    case 4: hipLaunchKernelGGL((pq_score_keys_kernel<4, RB, TB, GA>), grid, block, 0, st, a); return true;
+    case 1: launch_scores_one<1, RB, TB, GA>(a, grid, st); return true;
+    case 2: launch_scores_one<2, RB, TB, GA>(a, grid, st); return true;
+    case 4: launch_scores_one<4, RB, TB, GA>(a, grid, st); return true;
     default: return false;
   }
 }
@@ -248,6 +254,22 @@ extern "C" size_t pq_decode_workspace_bytes(const pq_layout* layout, int32_t n_s
 
 namespace pq {
 namespace {
+
+// Chunks of the score-only kernels: equal chunks of whole rounds of the 4 wavefronts, enough of
+// them for `groups_per_cu` resident work-groups on each compute unit (4 with the token-lane
+// kernel, 2 with the grouped quantizer's), at least 4 pages each.
+ChunkPlan plan_score_chunks(int32_t n_seqs, int32_t n_kv_heads, int32_t max_seq_len, int groups_per_cu) {
+  const int64_t max_pages = (static_cast<int64_t>(max_seq_len) + kGroup - 1) / kGroup;
+  const int64_t units = static_cast<int64_t>(n_seqs) * n_kv_heads;
+  const int64_t want = int64_t{256} * groups_per_cu;
+  const int64_t per_unit = std::max<int64_t>(1, (want + units - 1) / units);            // chunks per (sequence, KV head)
+  int64_t ppc = std::max<int64_t>(4, (max_pages + per_unit - 1) / per_unit);
+  ppc = (ppc + 3) & ~int64_t{3};
+  ChunkPlan p;
+  p.pages_per_chunk = static_cast<int32_t>(std::min<int64_t>(ppc, 256));                 // a wavefront keeps 64 page ids
+  p.n_chunks = static_cast<int32_t>((max_pages + p.pages_per_chunk - 1) / p.pages_per_chunk);
+  return p;
+}
 
 // Whether pq_decode_attention shares this launch out evenly and merges inside the attention kernel
 // (true), or launches one work-group per chunk and the merge kernel after it.
@@ -464,7 +486,13 @@ extern "C" int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_
     return PQ_ERR_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(block_table) | reinterpret_cast<uintptr_t>(seq_lens) | reinterpret_cast<uintptr_t>(scores)) & 3u)
     return PQ_ERR_INVALID_ARG;
-  const ChunkPlan plan = plan_chunks(n_seqs, layout->n_kv_heads, max_seq_len);
+  if (scores_stride >= (int64_t{1} << 28)) return PQ_ERR_UNSUPPORTED;   // 4 score rows are addressed with 32-bit byte offsets
+  const bool grouped = layout->angle_quantizer == PQ_ANGLE_GROUPED;
+#ifndef PQ_SCORE_GROUPS_PER_CU
+#define PQ_SCORE_GROUPS_PER_CU 4
+#endif
+  const ChunkPlan plan = plan_score_chunks(n_seqs, layout->n_kv_heads, max_seq_len, grouped ? 2 : PQ_SCORE_GROUPS_PER_CU);
+  if (plan.n_chunks > 65535) return PQ_ERR_UNSUPPORTED;   // grid.z
   DecodeArgs a = {};
   a.q = q;
   a.q_is_f32 = q_dtype == PQ_F32 ? 1 : 0;
@@ -493,7 +521,7 @@ extern "C" int pq_score_keys(const pq_layout* layout, const void* q, pq_dtype q_
     const int left = group_total - head0;
     const int G = left >= 4 ? 4 : (left >= 2 ? 2 : 1);
     a.head0 = head0;
-    if (!launch_scores(layout->r_bits * 10 + layout->t_bits, layout->angle_quantizer == PQ_ANGLE_GROUPED, G, a, grid, stream))
+    if (!launch_scores(layout->r_bits * 10 + layout->t_bits, grouped, G, a, grid, stream))
       return PQ_ERR_UNSUPPORTED;           // not reached: layout_supported() admits what is built
     e = hipGetLastError();
     head0 += G;

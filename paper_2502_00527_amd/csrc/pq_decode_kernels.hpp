@@ -282,6 +282,36 @@ __device__ __forceinline__ uint32_t add_byte(uint32_t x, uint32_t base) {
   return r;
 }
 
+// Fields of pair K of a unit: the radius code as a float, and `base` plus the byte offset of the
+// angle code's 16-byte table entry.
+template <int RB, int TB, int K>
+__device__ __forceinline__ void pair_fields(const Unit<(RB + TB) / 2>& u, uint32_t base, float& c, uint32_t& addr) {
+  constexpr int W = RB + TB;
+  if constexpr (RB == 4 && TB == 4) {
+    // byte K of the unit is (a << 4) | c: mask once per dword, then one op per field
+    const uint32_t d = u.d[K >> 2];
+    const uint32_t rad = d & 0x0f0f0f0fu, ang = d & 0xf0f0f0f0u;   // CSE'd across the dword's 4 pairs
+    c = byte_to_float<K & 3>(rad);
+    addr = add_byte<K & 3>(ang, base);                            // (a << 4) is the entry's byte offset
+  } else {
+    // generic widths: bit-field extract per field (after an alignbit if the symbol straddles
+    // two dwords), then v_lshl_add for the table address -- written as instructions because
+    // the compiler otherwise re-associates them into a longer shift/mask/add chain
+    constexpr int bit = K * W, wi = bit >> 5, sh = bit & 31;
+    uint32_t src = u.d[wi];
+    int off = sh;
+    if constexpr (sh + W > 32) {
+      src = __builtin_amdgcn_alignbit(u.d[wi + 1], u.d[wi], sh);
+      off = 0;
+    }
+    uint32_t cq, aq;
+    asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(cq) : "v"(src), "n"(off), "n"(RB));
+    asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(aq) : "v"(src), "n"(off + RB), "n"(TB));
+    asm("v_lshl_add_u32 %0, %1, 4, %2" : "=v"(addr) : "v"(aq), "v"(base));
+    c = byte_to_float<0>(cq);
+  }
+}
+
 // One pair step: part[h] += rho~ * T[h][pair K of this lane's block][angle code].
 // `lut_row0` is the LDS byte address of the lane's block (pair 16*row); radius
 // parameters are (s, z + s/2) so that rho~ = c * s + zz.
@@ -290,33 +320,10 @@ __device__ __forceinline__ void score_steps(const Unit<(RB + TB) / 2>& u, uint32
                                             const float (&sf)[16], const float (&zz)[16],
                                             float (&part)[G]) {
   if constexpr (K < 16) {
-    constexpr int W = RB + TB;
     constexpr int ROW = 16 << TB;
     float c;
     uint32_t addr;
-    if constexpr (RB == 4 && TB == 4) {
-      // byte K of the unit is (a << 4) | c: mask once per dword, then one op per field
-      const uint32_t d = u.d[K >> 2];
-      const uint32_t rad = d & 0x0f0f0f0fu, ang = d & 0xf0f0f0f0u;   // CSE'd across the dword's 4 pairs
-      c = byte_to_float<K & 3>(rad);
-      addr = add_byte<K & 3>(ang, lut_row0);                        // (a << 4) is the entry's byte offset
-    } else {
-      // generic widths: bit-field extract per field (after an alignbit if the symbol straddles
-      // two dwords), then v_lshl_add for the table address -- written as instructions because
-      // the compiler otherwise re-associates them into a longer shift/mask/add chain
-      constexpr int bit = K * W, wi = bit >> 5, sh = bit & 31;
-      uint32_t src = u.d[wi];
-      int off = sh;
-      if constexpr (sh + W > 32) {
-        src = __builtin_amdgcn_alignbit(u.d[wi + 1], u.d[wi], sh);
-        off = 0;
-      }
-      uint32_t cq, aq;
-      asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(cq) : "v"(src), "n"(off), "n"(RB));
-      asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(aq) : "v"(src), "n"(off + RB), "n"(TB));
-      asm("v_lshl_add_u32 %0, %1, 4, %2" : "=v"(addr) : "v"(aq), "v"(lut_row0));
-      c = byte_to_float<0>(cq);
-    }
+    pair_fields<RB, TB, K>(u, lut_row0, c, addr);
     const float rho = fmaf(c, sf[K], zz[K]);
     const Heads<G> t = lut_read<G, kPairs * ROW>(addr + K * ROW);
 #pragma unroll
@@ -325,6 +332,20 @@ __device__ __forceinline__ void score_steps(const Unit<(RB + TB) / 2>& u, uint32
   }
 }
 
+// The same step where every lane of the wavefront works on the same pair (lane = token): the
+// pair's radius parameters are the same for all lanes and stay in a scalar register as the
+// stored {fp16 s, fp16 z} word; v_fma_mix_f32 reads the halves directly (one scalar register per
+// instruction is what the hardware allows, and both halves are in one).
+__device__ __forceinline__ float midpoint_offset(uint32_t sz) {     // z + s / 2
+  float r;
+  asm("v_fma_mix_f32 %0, %1, 0.5, %1 op_sel:[0,0,1] op_sel_hi:[1,0,1]" : "=v"(r) : "s"(sz));
+  return r;
+}
+__device__ __forceinline__ float radius_from_code(float c, uint32_t sz, float zz) {   // c * s + zz
+  float r;
+  asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel_hi:[0,1,0]" : "=v"(r) : "v"(c), "s"(sz), "v"(zz));
+  return r;
+}
 // Residual keys (the un-quantized tail of a sequence): part[h] += sum over this lane's 32 dims
 // (pairs 16*row .. 16*row+15, i.e. dims 16*row.. and 64+16*row..) of k[dim] * q_h[dim].
 // kx / ky are the 16 fp16 x- and y-coordinates of the lane's pairs; `qs_row` is the LDS byte
@@ -988,9 +1009,10 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   }
 }
 
-// ---- query-key scores only (the kernel the paper times in Section 5.2) ------------------
-// Same table, same page walk and same pair steps as the attention kernel, without softmax and
-// values: every wavefront scores its pages and stores the raw q . k~ of valid tokens.
+// ---- query-key scores only, grouped angle quantizer --------------------------------------
+// Same tables, same page walk and same pair steps as the attention kernel, without softmax and
+// values: every wavefront scores its pages and stores the raw q . k~ of valid tokens.  (The
+// uniform grid is served by pq_score_tokens_kernel below; GA = false is not instantiated.)
 template <int G, int RB, int TB, bool GA>
 __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArgs a) {
   constexpr int W = RB + TB;
@@ -1104,6 +1126,216 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
       if (owner && tok < nv_cur && pi != res_page) out_row[static_cast<int64_t>(pi) * kGroup + tok] = sc;
     }
     rc_cur = rc_nxt; rp_cur = rp_nxt; nv_cur = nv_nxt;
+  }
+}
+
+// ---- query-key scores only (the kernel the paper times in Section 5.2) ------------------
+// Uniform angle grid.  Same table as the attention kernels; the lanes of a wavefront are 64
+// consecutive TOKENS of a page and walk the 64 pairs together, block of 16 pairs by block, both
+// halves of the page per block.  Because all lanes read the same pair's table row (16 bytes per
+// angle state, at most 512 bytes: every LDS bank at most once, equal states broadcast), the
+// gather is free of bank conflicts whatever the codes are; the pair's radius parameters are
+// wavefront-uniform and come through scalar loads, one block (64 bytes) at a time, each block
+// replaced by the next page's as soon as it has been used; and a head's scores of 64 tokens leave
+// as whole cache lines.  Per pair and token: the field extraction, one conversion, one
+// multiply-add for the radius, G for the heads.
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+#define PQ_CONST __attribute__((address_space(4)))
+struct BlockParams {
+  uint32_t sz[16];     // {fp16 s, fp16 z} of the block's 16 pairs
+};
+// `page_params` is wavefront-uniform and points to valid memory
+__device__ __forceinline__ BlockParams load_block_params(const uint32_t* page_params, int block) {
+  const u32x16 v = *reinterpret_cast<const PQ_CONST u32x16*>(reinterpret_cast<uintptr_t>(page_params + block * kPairsPerUnit));
+  BlockParams p;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) p.sz[i] = v[i];
+  return p;
+}
+
+// A page's 128 steps of a lane -- step S: pair block kBlockOrder[S / 32], half of the page
+// (S / 16) % 2, pair S % 16 of the block -- with the table reads kScorePipe steps ahead of their
+// use.  Written out step by step, each step closed for the instruction scheduler: under this
+// kernel's register budget the compiler otherwise issues one read, waits for it, and so on.  As
+// a block's last step goes by, its parameters are replaced by the next page's; as a unit's last
+// read is issued, the unit is replaced by the next page's.
+// The sum over the 64 pairs is associated exactly as in the attention kernels, where the four
+// 16-lane rows each sum one block and fold_rows adds (block 0 + block 2) + (block 1 + block 3):
+// a score from here equals, bit for bit, the one the attention kernels compute.
+#ifndef PQ_SCORE_PIPE
+#define PQ_SCORE_PIPE 4
+#endif
+constexpr int kScorePipe = PQ_SCORE_PIPE;
+template <int G, int RB, int TB>
+struct PageWalk {
+  static constexpr int W = RB + TB;
+  static constexpr int UB = 2 * W;
+  static constexpr int ROW = 16 << TB;
+  static constexpr int kRing = kScorePipe + 1;   // reads in flight, plus the one in use
+  Unit<W / 2> cu[2 * kBlocks];                   // unit (half, block) at [half * kBlocks + block]
+  BlockParams par[kBlocks];
+  float zz[16];
+  float c[kRing];
+  Heads<G> t[kRing];
+  float cur[2][G], sum02[2][G], sum13[2][G];     // per half of the page: the running block, and the pairs of blocks
+  float score[2][G];
+  uint32_t lut_base, voff_codes;
+
+  static constexpr uint32_t unit_at(int half, int b) { return static_cast<uint32_t>((b * kGroup + half * 64) * UB); }
+  static constexpr int block_of(int S) { return ((S / 32) >> 1) | (((S / 32) & 1) << 1); }   // 0, 2, 1, 3
+
+  template <int S>
+  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rc_nxt) {
+    if constexpr (S < 128) {
+      constexpr int b = block_of(S), half = (S / 16) % 2, K = S % 16;
+      uint32_t addr;
+      pair_fields<RB, TB, K>(cu[half * kBlocks + b], lut_base, c[S % kRing], addr);
+      t[S % kRing] = lut_read<G, kPairs * ROW>(addr + (b * kPairsPerUnit + K) * ROW);
+      if constexpr (K == 15) cu[half * kBlocks + b] = load_unit<W>(rc_nxt, voff_codes, unit_at(half, b));
+    }
+  }
+  template <int S>
+  __device__ __forceinline__ void steps(__amdgpu_buffer_rsrc_t rc_nxt, const uint32_t* pp_nxt) {
+    if constexpr (S < 128) {
+      constexpr int j = S / 32, b = block_of(S), half = (S / 16) % 2, K = S % 16;
+      if constexpr (S % 32 == 0) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) zz[k] = midpoint_offset(par[b].sz[k]);
+      }
+      issue<S + kScorePipe>(rc_nxt);
+      const float rho = radius_from_code(c[S % kRing], par[b].sz[K], zz[K]);
+#pragma unroll
+      for (int h = 0; h < G; ++h) cur[half][h] = fmaf(rho, t[S % kRing].v[h], K == 0 ? 0.f : cur[half][h]);
+      if constexpr (K == 15) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          if constexpr (j == 0) sum02[half][h] = cur[half][h];
+          else if constexpr (j == 1) sum02[half][h] += cur[half][h];
+          else if constexpr (j == 2) sum13[half][h] = cur[half][h];
+          else score[half][h] = sum02[half][h] + (sum13[half][h] + cur[half][h]);
+        }
+      }
+      if constexpr (S % 32 == 31) par[b] = load_block_params(pp_nxt, b);
+      __builtin_amdgcn_sched_barrier(0);
+      steps<S + 1>(rc_nxt, pp_nxt);
+    }
+  }
+  // scores of the page in cu / par (left in `score`); cu / par then hold the next page
+  __device__ __forceinline__ void run(__amdgpu_buffer_rsrc_t rc_nxt, const uint32_t* pp_nxt) {
+    issue<0>(rc_nxt);
+    issue<1>(rc_nxt);
+    if constexpr (kScorePipe > 2) issue<2>(rc_nxt);
+    if constexpr (kScorePipe > 3) issue<3>(rc_nxt);
+    if constexpr (kScorePipe > 4) issue<4>(rc_nxt);
+    if constexpr (kScorePipe > 5) issue<5>(rc_nxt);
+    static_assert(kScorePipe >= 2 && kScorePipe <= 6, "reads in flight");
+    steps<0>(rc_nxt, pp_nxt);
+  }
+};
+
+#ifndef PQ_SCORE_WAVES
+#define PQ_SCORE_WAVES 4
+#endif
+template <int G, int RB, int TB>
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(PQ_SCORE_WAVES, PQ_SCORE_WAVES)))
+void pq_score_tokens_kernel(const DecodeArgs a) {
+  constexpr int W = RB + TB;
+  constexpr int UB = 2 * W;
+  constexpr int NA = 1 << TB;
+  constexpr int ROW = NA * 16;
+  __shared__ __attribute__((aligned(16))) uint8_t lut[kPairs * ROW];
+  __shared__ __attribute__((aligned(16))) float q_lds[kHeadDim][4];   // q[dim][head]: table build, residual keys
+  __shared__ float2 trig[kMaxAngleBins];
+
+  const int kvh = blockIdx.x, seq = blockIdx.y, chunk = blockIdx.z;
+  const int L = min(a.seq_lens[seq], a.max_seq_len);
+  if (L <= 0) return;
+  const int n_pages = (L + kGroup - 1) / kGroup;
+  const int page0 = chunk * a.pages_per_chunk;
+  if (page0 >= n_pages) return;
+  const int npg = min(a.pages_per_chunk, n_pages - page0);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t voff_codes = lane * UB;
+  constexpr uint32_t kCodesBytes = kBlocks * kGroup * UB;
+
+  const int res_page = (a.residual != nullptr && (L % kGroup) != 0) ? L / kGroup : -1;
+  const int n_w = npg > wave ? (npg - wave + kWaves - 1) / kWaves : 0;   // pages of this wavefront: wave, wave + 4, ...
+  int pid_lane = -1;
+  if (lane < n_w) {
+    const int64_t pid = a.block_table[static_cast<int64_t>(seq) * a.max_pages_per_seq + page0 + wave + kWaves * lane];
+    if (pid >= 0 && pid < a.n_pool_pages) pid_lane = static_cast<int>(pid);
+  }
+  // codes descriptor, parameter address and valid tokens of the wavefront's k-th page; a masked
+  // page or the residual group reads nothing (empty descriptor; parameters of pool page 0, unused)
+  auto page_setup = [&](int k, __amdgpu_buffer_rsrc_t& rc, const uint32_t*& pp, int& nv) {
+    const int pid = k < n_w ? __builtin_amdgcn_readlane(pid_lane, k) : -1;
+    const bool ok = pid >= 0;
+    const int64_t ph = (ok ? static_cast<int64_t>(pid) : 0) * a.n_kv_heads + kvh;
+    nv = ok ? min(kGroup, L - (page0 + wave + kWaves * k) * kGroup) : 0;
+    const bool packed = ok && (page0 + wave + kWaves * k) != res_page;
+    rc = make_rsrc(a.codes + ph * kCodesBytes, packed ? kCodesBytes : 0u);
+    pp = a.params + ph * kPairs;
+  };
+  __amdgpu_buffer_rsrc_t rc_cur, rc_nxt;
+  const uint32_t* pp_cur;
+  const uint32_t* pp_nxt;
+  int nv_cur, nv_nxt;
+  page_setup(0, rc_cur, pp_cur, nv_cur);
+  PageWalk<G, RB, TB> w;
+  w.voff_codes = voff_codes;
+#pragma unroll
+  for (int b = 0; b < kBlocks; ++b) w.par[b] = load_block_params(pp_cur, b);
+#pragma unroll
+  for (int b = 0; b < kBlocks; ++b)
+#pragma unroll
+    for (int half = 0; half < 2; ++half) w.cu[half * kBlocks + b] = load_unit<W>(rc_cur, voff_codes, w.unit_at(half, b));
+
+  load_query_lds<G>(q_lds, trig, a, (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * kHeadDim, tid);
+  __syncthreads();
+  build_uniform_table<TB>(lut, q_lds, trig, tid, kThreads);
+  __syncthreads();
+
+  float* const out_rows = a.scores + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * a.scores_stride;
+
+  // the G heads' rows of scores through one descriptor (the host keeps 4 rows under 4 GiB): a
+  // lane's offset is its token, the head's row the scalar offset
+  const uint32_t row_bytes = static_cast<uint32_t>(a.scores_stride) * 4u;
+  const __amdgpu_buffer_rsrc_t rs_out = make_rsrc(out_rows, static_cast<uint32_t>(G - 1) * row_bytes + static_cast<uint32_t>(L) * 4u);
+  w.lut_base = lds_addr(lut);
+  for (int i = 0; i < n_w; ++i) {
+    const int pi = page0 + wave + kWaves * i;
+    page_setup(i + 1, rc_nxt, pp_nxt, nv_nxt);
+    w.run(rc_nxt, pp_nxt);
+    // Unconditional stores (a conditional one would let the compiler move the page's arithmetic
+    // behind the condition, away from its table reads): what must not be stored -- tokens past the
+    // sequence end, a page without scores of its own -- gets an offset outside the descriptor.
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const bool valid = pi != res_page && half * 64 + lane < nv_cur;
+      const uint32_t vo = valid ? (static_cast<uint32_t>(pi) * kGroup + half * 64 + lane) * 4u : 0xffffffffu;
+#pragma unroll
+      for (int h = 0; h < G; ++h) __builtin_amdgcn_raw_buffer_store_b32(f2u(w.score[half][h]), rs_out, vo, h * row_bytes, kAuxStream);
+    }
+    rc_cur = rc_nxt; pp_cur = pp_nxt; nv_cur = nv_nxt;
+  }
+
+  // Last (the page loop's registers are free by now): with a residual buffer the last, incomplete
+  // group of the sequence is fp16 keys: plain dot products, by the wavefront that owns the
+  // group's page, in the lane layout of the attention kernels (lane = (pair block row, token
+  // col), folded over the rows).
+  if (res_page >= page0 + wave && res_page < page0 + npg && ((res_page - page0 - wave) & (kWaves - 1)) == 0) {
+    const int row = lane >> 4, col = lane & 15;
+    const int my_head = (G == 4) ? row : (G == 2 ? (row >> 1) : 0);
+    const bool owner = (G == 4) || (G == 2 && (row & 1) == 0) || (G == 1 && row == 0);
+    const int nv_res = L - res_page * kGroup;
+    residual_scores<G>(a.residual + (static_cast<int64_t>(seq) * a.n_kv_heads + kvh) * (kGroup * kHeadDim), nv_res,
+                       lds_addr(q_lds), row, col, [&](int s, Folded<G> v) {
+                         const int tok = s * 16 + col;
+                         if (owner && tok < nv_res)
+                           out_rows[my_head * a.scores_stride + static_cast<int64_t>(res_page) * kGroup + tok] = v.v[0];
+                       });
   }
 }
 
