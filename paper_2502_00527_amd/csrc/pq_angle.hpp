@@ -69,6 +69,55 @@ PQ_HD inline uint32_t angle_bin(float x, float y, const double* tan_edge) {
   return origin * (NB / 2) + (1u ^ origin) * code;
 }
 
+// The same bin for a pair strictly inside an octant (x != 0, y != 0, |x| != |y|; `interior` says
+// whether that holds -- if not, the result is meaningless and angle_bin decides).  There the
+// octant is a table look-up on (x < 0, y < 0, |y| > |x|): entry = first bin of the octant, plus
+// S - 1 in odd octants, where the angle runs against the ratio mn / mx and the count of passed
+// edges is subtracted; since the count is below S, both cases are one XOR with the entry.  (A
+// float64 product that equals mn exactly is counted as passed in both directions; angle_bin
+// counts it as passed towards the upper bin.  Edges have irrational slopes, so this is a
+// statement about rounding noise, not about points on an edge.)
+namespace detail {
+constexpr uint32_t octant_of(int idx) {          // idx = (x < 0) + 2 (y < 0) + 4 (|y| > |x|)
+  constexpr uint32_t o[8] = {4, 7, 3, 0, 5, 6, 2, 1};
+  return o[idx];
+}
+template <int TB>
+constexpr uint32_t octant_entries(int gt) {      // 4 entries of 8 bits, for idx = 4 gt .. 4 gt + 3
+  constexpr int NB = 1 << TB;
+  constexpr int S = NB >= 8 ? NB / 8 : 1;
+  uint32_t w = 0;
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t o = octant_of(4 * gt + i);
+    const uint32_t e = TB == 2 ? (o >> 1) : o * S + (o & 1u) * (S - 1);
+    w |= e << (8 * i);
+  }
+  return w;
+}
+}  // namespace detail
+
+template <int TB>
+PQ_HD inline uint32_t angle_bin_interior(float x, float y, const double* tan_edge, bool& interior) {
+  constexpr int NB = 1 << TB;
+  constexpr int S = NB >= 8 ? NB / 8 : 1;
+  constexpr uint32_t lo = detail::octant_entries<TB>(0), hi = detail::octant_entries<TB>(1);
+  uint32_t bx, by;
+  __builtin_memcpy(&bx, &x, 4);
+  __builtin_memcpy(&by, &y, 4);
+  const float ax = __builtin_fabsf(x), ay = __builtin_fabsf(y);
+  const float mnf = ax < ay ? ax : ay, mxf = ax < ay ? ay : ax;
+  interior = mnf != 0.f && mnf != mxf;
+  const uint32_t shift = ((bx >> 28) & 8u) | ((by >> 27) & 16u);      // 8 * ((x < 0) + 2 (y < 0))
+  uint32_t code = ((ay > ax ? hi : lo) >> shift) & 0xffu;
+  if (S > 1) {
+    const double mn = mnf, mx = mxf;
+    uint32_t passed = 0;
+    for (int k = 1; k < S; ++k) passed += mx * tan_edge[k] <= mn;
+    code ^= passed;
+  }
+  return code;
+}
+
 // v rounded to the nearest fp16 value, ties to even, returned as a double (|v| < 65504).  One
 // rounding, straight from float64: the quantum is 2^(e - 10) for |v| in [2^e, 2^(e+1)), and 2^-24
 // below the smallest normal fp16.  Used for the 16-bit parameters of the grouped angle quantizer,

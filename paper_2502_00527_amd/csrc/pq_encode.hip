@@ -155,7 +155,12 @@ __device__ __forceinline__ void encode_group(const KT* keys, int64_t token_strid
           tmn[e] = fmin(tmn[e], t);
           tmx[e] = fmax(tmx[e], t);
         } else {
-          ang[it][e >> 2] |= angle_bin<TB>(x[e], y[e], tan_edge) << (8 * (e & 3));
+          // the short rule; the full one only when some lane's pair sits on an axis, a diagonal or
+          // the origin (a few per cent of the wavefront steps with fp16 keys)
+          bool interior;
+          uint32_t bin = angle_bin_interior<TB>(x[e], y[e], tan_edge, interior);
+          if (__builtin_amdgcn_ballot_w64(!interior) != 0) bin = interior ? bin : angle_bin<TB>(x[e], y[e], tan_edge);
+          ang[it][e >> 2] |= bin << (8 * (e & 3));
         }
       }
     } else {

@@ -22,6 +22,8 @@ def host_lib(tmp_path_factory):
     lib = ctypes.CDLL(str(out))
     lib.angle_bins_host.restype = ctypes.c_int
     lib.angle_bins_host.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p]
+    lib.angle_bins_interior_host.restype = ctypes.c_int
+    lib.angle_bins_interior_host.argtypes = lib.angle_bins_host.argtypes
     lib.round_to_half_host.restype = None
     lib.round_to_half_host.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
     return lib
@@ -64,6 +66,28 @@ def test_angle_rule_matches_oracle(host_lib, t):
     # the two float64 evaluations may differ only within ~1e-15 rad of an irrational edge
     assert not np.any(bad & (edge > 1e-12)), (x[bad][:5], y[bad][:5], got[bad][:5], want[bad][:5])
     assert bad.sum() <= 2
+
+
+@pytest.mark.parametrize("t", [2, 3, 4, 5])
+def test_interior_rule_agrees_with_the_full_rule(host_lib, t):
+    """The encoder's short rule for pairs strictly inside an octant gives the full rule's bin, and
+    declines exactly the pairs on an axis, a diagonal or the origin."""
+    x, y = _inputs()
+    x = np.ascontiguousarray(x, np.float32)
+    y = np.ascontiguousarray(y, np.float32)
+    full = _host_bins(host_lib, x, y, t)
+    got = np.empty(x.size, np.int32)
+    assert host_lib.angle_bins_interior_host(x.ctypes.data, y.ctypes.data, x.size, t, got.ctypes.data) == 0
+    on_boundary = (x == 0) | (y == 0) | (np.abs(x) == np.abs(y))
+    assert np.array_equal(got == -1, on_boundary)
+    assert on_boundary.sum() > 300 and (~on_boundary).sum() > 500000
+    want, edge = polar.angle_bin(x, y, t)
+    inside = ~on_boundary
+    bad = inside & (got != full)
+    assert not np.any(bad & (edge > 1e-12))
+    assert bad.sum() <= 2
+    bad = inside & (got != want)
+    assert not np.any(bad & (edge > 1e-12)) and bad.sum() <= 2
 
 
 def test_round_to_half_is_one_nearest_even_rounding(host_lib):
