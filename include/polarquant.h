@@ -169,8 +169,10 @@ int pq_encode_values(const pq_layout* layout, int32_t v_bits, const void* values
  *
  *   q             device [n_seqs][n_q_heads][d], post-RoPE, q_dtype PQ_F16 or PQ_F32.
  *                 Query head h reads KV head h / (n_q_heads / n_kv_heads); the ratio may be
- *                 1 .. 16.  Kernels serve 4, 2 or 1 query heads per pass over the cache, so a
- *                 ratio of 1, 2 or 4 reads the cache once, 8 twice, 6 = 4 + 2 twice, ...
+ *                 1 .. 16.  Kernels serve 8, 4, 2 or 1 query heads per pass over the cache (8
+ *                 with fp16 values, in launches large enough for the role-specialised kernel,
+ *                 see pq_decode_kernel_name), so a ratio of 1, 2, 4 (or 8) reads the cache once,
+ *                 6 = 4 + 2 twice, 12 = 8 + 4 twice, ...
  *   block_table   device int32 [n_seqs][max_pages_per_seq]: page of tokens
  *                 [i*g, (i+1)*g) of each sequence; entries past a sequence's last page
  *                 are ignored
@@ -197,7 +199,10 @@ int pq_encode_values(const pq_layout* layout, int32_t v_bits, const void* values
  *   workspace     device, >= pq_decode_workspace_bytes(layout, n_seqs, n_q_heads, max_seq_len),
  *                 256-byte aligned; contents are scratch
  *
- * Scores are accumulated in fp32; probabilities and outputs in fp32.
+ * Scores, softmax statistics and outputs are fp32.  The probabilities that weight the values are
+ * fp32 too, except with quantized values and in 8-head passes, where they are rounded to fp16
+ * (pairs of tokens for the two-term fp16 dot product with an fp32 accumulator; with quantized
+ * values the token's fp16 scale is folded in before the rounding).
  */
 int pq_decode_attention(const pq_layout* layout, const void* q, pq_dtype q_dtype, int32_t n_seqs,
                         int32_t n_q_heads, const void* codes_pool, const void* params_pool,

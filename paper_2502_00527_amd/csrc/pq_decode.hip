@@ -6,14 +6,7 @@
 #include "pq_decode_kernels.hpp"
 #include "pq_decode_roles.hpp"
 
-// Which attention kernel serves fp16 values with the uniform angle grid: the role-specialised
-// one (1) or the one whose wavefronts alternate between a score and a value phase (0).
-#ifndef PQ_USE_ROLES
-#define PQ_USE_ROLES 1
-#endif
-
-
-// Scratch of pq_decode_attention_static: the chunk partials live here instead of in a
+// Scratch of pq_decode_attention_static: partials and arrival words live here instead of in a
 // caller-supplied workspace.  One copy per GPU, at its own address on each.
 static __device__ __align__(256) unsigned char scratch[PQ_STATIC_SCRATCH_BYTES];
 
@@ -160,7 +153,7 @@ AttentionKernel choose_attention_kernel(const pq_layout* l, int32_t v_bits, int3
   // specialised ones leave two of them short (measured at the GQA shape, 4-bit values: 150 against
   // 178 us; with 1 or 2 heads per KV head the specialised kernel wins, 61 against 64 us at the MHA shape).
   const bool roles_fit = v_bits == 16 || n_q_heads / l->n_kv_heads <= 2;
-  if (PQ_USE_ROLES && l->angle_quantizer == PQ_ANGLE_UNIFORM && roles_fit && n_seqs <= kBalancedMaxSeqs &&
+  if (l->angle_quantizer == PQ_ANGLE_UNIFORM && roles_fit && n_seqs <= kBalancedMaxSeqs &&
       bound < (int64_t{1} << 31) && balanced_groups(l, n_seqs, max_seq_len) >= 256)
     return AttentionKernel::kRoles;
   return AttentionKernel::kPartials;
@@ -274,12 +267,8 @@ ChunkPlan plan_score_chunks(int32_t n_seqs, int32_t n_kv_heads, int32_t max_seq_
 // Whether pq_decode_attention shares this launch out evenly and merges inside the attention kernel
 // (true), or launches one work-group per chunk and the merge kernel after it.
 bool merges_in_kernel(const pq_layout* l, int32_t v_bits, int32_t n_seqs, int32_t n_q_heads, int32_t max_seq_len) {
-#ifdef PQ_FORCE_GRID
-  return false;
-#else
   if (choose_attention_kernel(l, v_bits, n_seqs, n_q_heads, max_seq_len) != AttentionKernel::kRoles) return false;
   return static_cast<int64_t>(n_seqs) * l->n_kv_heads * kArriveFan >= balanced_groups(l, n_seqs, max_seq_len);
-#endif
 }
 
 // Everything the decode entry points have in common: argument checks, kernel arguments, and the

@@ -8,12 +8,17 @@
 // pulled out of the token loop.  Softmax and the fp16 value aggregation that
 // consume the scores are fused behind it (standard attention, Section 2).
 //
-// Mapping to the machine.  One work-group = 4 wavefronts = one (sequence, KV
-// head, chunk of pages); the table of all query heads that share the KV head
-// lives in LDS with the heads interleaved (one 16-byte entry serves 4 heads).
-// Each wavefront owns whole pages (= quantization groups), so a page's radius
-// parameters are loaded once into registers and no work-group barrier is
-// needed inside the loop:
+// This header holds what the decode kernels share (streaming loads, table builds, pair steps,
+// value steps, residual keys) and two of the kernels: pq_decode_partials_kernel, whose
+// wavefronts alternate between a score and a value phase, and the score-only kernels.  The
+// attention kernel that serves large launches, with wavefronts specialised by role, is in
+// pq_decode_roles.hpp; how a launch is shared out and merged inside the kernel is in
+// pq_decode_sched.hpp.
+//
+// Mapping to the machine in the attention kernels.  A work-group is 4 wavefronts; the table of
+// all query heads that share the KV head lives in LDS with the heads interleaved (one 16-byte
+// entry serves 4 heads).  Pages (= quantization groups) are owned by one wavefront, so a page's
+// radius parameters are loaded once into registers:
 //   score  : lane = (pair block q = lane / 16, token tk = lane % 16).  One
 //            128-bit (96-bit for w = 6) load brings the 16 symbols of pairs
 //            16q .. 16q+15; the 16 lanes of a row read 16 consecutive units.
@@ -22,8 +27,9 @@
 //   softmax: online, per page, in the log2 domain (running max m, sum l).
 //   values : lane = (token slot lane / 16, dims 8*(lane % 16) ..+7); 128-bit
 //            loads of fp16 rows, probabilities broadcast from LDS.
-// A last step folds the four wavefronts' (m, l, acc) into one partial per
-// (sequence, query head, chunk); pq_decode_merge_kernel combines the chunks.
+// In pq_decode_partials_kernel a last step folds the four wavefronts' (m, l, acc) into one
+// partial per (sequence, query head, chunk); pq_decode_merge_kernel combines the chunks.
+// (The score-only kernel of the uniform grid maps lanes to tokens instead: see PageWalk.)
 // No MFMA: the hot loop is a gather-accumulate.
 //
 // Grouped angle quantizer (Section 3.2 as printed; template flag GA): the angle levels of a
