@@ -241,14 +241,20 @@ def test_results_are_deterministic():
 
 @pytest.mark.parametrize("name", ["gqa_ragged_tail", "tiny33_fp32", "group_of_two", "ragged_pages", "bits_r5t3",
                                   "group_of_six", "grouped_angles_gqa", "grouped_angles_edge_lengths",
-                                  "grouped_angles_r3t3_many_chunks", "grouped_angles_r3t5", "grouped_angles_r4t2"])
+                                  "grouped_angles_r3t3_many_chunks", "grouped_angles_r3t5", "grouped_angles_r4t2",
+                                  # launches of hundreds of work-groups, several chunks per sequence: every
+                                  # (r, t) of the token-lane kernel, 1 / 2 / 4 heads per pass, fp32 queries
+                                  "big_r4t4_g4", "big_r3t3_g4", "big_r5t3_g1", "big_r3t5_g2", "big_r4t2_g1",
+                                  "big_r2t4_g2", "big_fp32_r3t3_g2", "big_group_of_seven_r4t2", "big_ragged_r3t3",
+                                  "few_units_group_of_four_r3t3"])
 def test_score_keys_entry_point(name):
     """pq_score_keys (the query-key product alone) against the oracle's dequantize-then-dot scores,
     and against the scores pq_decode_attention reports for the same cache."""
     from paper_2502_00527_amd import pq_score_keys
     from paper_2502_00527_amd.cache import build_device_cache
 
-    wl, lens = SMALL[name]
+    wl, lens = SMALL[name] if name in SMALL else LARGE_GRID[name]
+    lens = _lengths(wl, lens)
     cache = build_device_cache(wl, lens=lens)
     S, Hq = wl.n_seqs, wl.n_q_heads
     got = torch.full((S, Hq, cache.max_seq_len), float("nan"), dtype=torch.float32, device="cuda:0")
