@@ -125,6 +125,30 @@ __device__ __forceinline__ float row_sum(float x) {
   x += __shfl_xor(x, 2);
   return x + __shfl_xor(x, 1);
 }
+// Maximum / sum over all 64 lanes, result in every lane: inside a row of 16 by DPP (lane ^ 1,
+// lane ^ 2, mirror within 8, mirror within 16), across the rows by the two lane-swap instructions.
+template <int CTRL>
+__device__ __forceinline__ float dpp_of(float x) {
+  return u2f(static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(f2u(x)), CTRL, 0xf, 0xf, true)));
+}
+__device__ __forceinline__ float wave_max(float x) {
+  x = fmaxf(x, dpp_of<0xB1>(x));      // quad_perm(1,0,3,2)
+  x = fmaxf(x, dpp_of<0x4E>(x));      // quad_perm(2,3,0,1)
+  x = fmaxf(x, dpp_of<0x141>(x));     // row_half_mirror
+  x = fmaxf(x, dpp_of<0x140>(x));     // row_mirror
+  auto r = __builtin_amdgcn_permlane16_swap(f2u(x), f2u(x), false, false);
+  x = fmaxf(u2f(r[0]), u2f(r[1]));
+  auto q = __builtin_amdgcn_permlane32_swap(f2u(x), f2u(x), false, false);
+  return fmaxf(u2f(q[0]), u2f(q[1]));
+}
+__device__ __forceinline__ float wave_sum_f(float x) {
+  x += dpp_of<0xB1>(x);
+  x += dpp_of<0x4E>(x);
+  x += dpp_of<0x141>(x);
+  x += dpp_of<0x140>(x);
+  return sum_rows(x);
+}
+
 // Sum of the four 16-lane rows' partial scores: with 4 query heads row h ends with head h's
 // score (transposing fold), with 2 heads rows 0-1 / 2-3, with 1 head every row; with 8 heads row h
 // ends with the scores of heads h and h + 4 (two transposing folds).
@@ -1168,11 +1192,7 @@ __device__ __forceinline__ BlockParams load_block_params(const uint32_t* page_pa
 // The sum over the 64 pairs is associated exactly as in the attention kernels, where the four
 // 16-lane rows each sum one block and fold_rows adds (block 0 + block 2) + (block 1 + block 3):
 // a score from here equals, bit for bit, the one the attention kernels compute.
-#ifndef PQ_SCORE_PIPE
-#define PQ_SCORE_PIPE 4
-#endif
-constexpr int kScorePipe = PQ_SCORE_PIPE;
-template <int G, int RB, int TB>
+template <int G, int RB, int TB, int kScorePipe = 4>
 struct PageWalk {
   static constexpr int W = RB + TB;
   static constexpr int UB = 2 * W;
@@ -1236,6 +1256,13 @@ struct PageWalk {
     if constexpr (kScorePipe > 5) issue<5>(rc_nxt);
     static_assert(kScorePipe >= 2 && kScorePipe <= 6, "reads in flight");
     steps<0>(rc_nxt, pp_nxt);
+    // The scores exist here, whatever the caller's control flow does with them: left to itself
+    // the compiler moves a head's 64 multiply-adds behind a later condition under which the score
+    // is used, away from their table reads, whose results then wait in (spilled) registers.
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int h = 0; h < G; ++h) asm volatile("" : "+v"(score[half][h]));
   }
 };
 

@@ -11,16 +11,19 @@
 namespace pq {
 namespace {
 
+template <int G, int RB, int TB, int VB>
+void launch_one(const DecodeArgs& a, int n_wg, hipStream_t st) {
+  hipLaunchKernelGGL((pq_decode_roles_kernel<G, RB, TB, VB, PQ_ROLES_BALANCED>), dim3(n_wg), dim3(kRoleThreads), 0, st, a);
+}
 template <int RB, int TB, int VB>
 bool launch_g(int G, const DecodeArgs& a, int n_wg, hipStream_t st) {
-  const dim3 grid(n_wg), block(kRoleThreads);
   switch (G) {
-    case 1: hipLaunchKernelGGL((pq_decode_roles_kernel<1, RB, TB, VB, PQ_ROLES_BALANCED>), grid, block, 0, st, a); return true;
-    case 2: hipLaunchKernelGGL((pq_decode_roles_kernel<2, RB, TB, VB, PQ_ROLES_BALANCED>), grid, block, 0, st, a); return true;
-    case 4: hipLaunchKernelGGL((pq_decode_roles_kernel<4, RB, TB, VB, PQ_ROLES_BALANCED>), grid, block, 0, st, a); return true;
+    case 1: launch_one<1, RB, TB, VB>(a, n_wg, st); return true;
+    case 2: launch_one<2, RB, TB, VB>(a, n_wg, st); return true;
+    case 4: launch_one<4, RB, TB, VB>(a, n_wg, st); return true;
     case 8:
       if constexpr (VB == 16) {
-        hipLaunchKernelGGL((pq_decode_roles_kernel<8, RB, TB, VB, PQ_ROLES_BALANCED>), grid, block, 0, st, a);
+        launch_one<8, RB, TB, VB>(a, n_wg, st);
         return true;
       }
       return false;

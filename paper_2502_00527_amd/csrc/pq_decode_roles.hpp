@@ -1,19 +1,23 @@
 // Attention kernel with wavefronts specialised by role (uniform angle grid).
 //
 // A work-group takes an equal share of the launch's pages (pq_decode_sched.hpp) and works through
-// it segment by segment; a segment is a run of pages of one (sequence, KV head).  Table, layouts,
-// score steps and value steps are those of pq_decode_partials_kernel (pq_decode_kernels.hpp); what
-// differs is who does what.  The four wavefronts form two pairs; a pair takes every second page
-// of the segment.  In a pair the SCORE wavefront (0 or 1) streams the codes, runs the table-lookup
-// product and the online softmax and leaves the page's probabilities and rescaling factor in
-// LDS; the VALUE wavefront (2 or 3) streams the value rows and aggregates them with the
-// probabilities of the page the score wavefront finished one step earlier.  One work-group
-// barrier per step hands a probability buffer over (two buffers per pair).  Each role keeps only
-// its own state in registers (codes, parameters and softmax state on one side; accumulators and
-// the ring of value rows on the other), so three wavefronts fit a SIMD, and because wavefront w
-// of a work-group runs on SIMD w, two SIMDs of a compute unit do arithmetic-heavy scoring while
-// the other two keep the memory system busy -- instead of every wavefront alternating between a
-// phase that waits for memory and one that does not touch it.
+// it segment by segment; a segment is a run of pages of one (sequence, KV head).  The four
+// wavefronts form two pairs; a pair takes every second page of the segment.  In a pair the SCORE
+// wavefront (0 or 1) streams the codes, runs the table-lookup product and the online softmax
+// and leaves the page's probabilities and rescaling factor in LDS; the VALUE wavefront (2 or 3)
+// streams the value rows and aggregates them with the probabilities of the page the score
+// wavefront finished one step earlier.  One work-group barrier per step hands a probability
+// buffer over (two buffers per pair).  Each role keeps only its own state in registers, so three
+// wavefronts fit a SIMD, and arithmetic-heavy scoring and memory-heavy aggregation overlap
+// instead of every wavefront alternating between a phase that waits for memory and one that
+// does not touch it.
+//
+// The score wavefront's lanes are 64 consecutive tokens of the page (PageWalk in
+// pq_decode_kernels.hpp, the score-only kernel's walk): all lanes look up the same pair, so the
+// table reads have no bank conflicts and the pair's radius parameters sit in scalar registers; a
+// lane ends a page with the scores of tokens lane and 64 + lane for all G heads, and a head's
+// softmax statistics are wavefront-wide reductions.  The value wavefront's lanes are (token slot,
+// 8 dims) as in pq_decode_partials_kernel, whose value steps it shares.
 //
 // Every wavefront of the work-group executes the same number of barriers: segment list and step
 // count are computed from wavefront-uniform values that all four wavefronts derive alike.
@@ -164,48 +168,50 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
     pids.start(a.block_table + static_cast<int64_t>(seq) * a.max_pages_per_seq + page0 + pair, a.n_pool_pages, n_p, lane);
 
     if (scorer) {
-      // =========================== SCORE wavefront ===========================
-      const uint32_t lut_row0 = lds_addr(lut) + row * (kPairsPerUnit * ROW);
-      const uint32_t voff_codes = (row * kGroup + col) * UB;
-      const uint32_t voff_params = row * (kPairsPerUnit * 4);
-      float m_run[NH], l_run[NH], z_run = 0.f;
+      // ================ SCORE wavefront: lanes = tokens (PageWalk) ================
+      // The lanes are 64 consecutive tokens of a page and walk the pairs together: table reads
+      // without bank conflicts, radius parameters in scalar registers.  A lane ends a page with
+      // the scores of tokens lane and 64 + lane for all G heads; the softmax statistics of a
+      // head are wavefront-wide reductions and therefore uniform.  Probabilities go to LDS in
+      // the same layouts as below, so the value wavefront does not know the difference.
+      constexpr int kPipe = G == 8 ? 3 : 4;                          // table reads in flight (8 heads: two reads per step)
+      PageWalk<G, RB, TB, kPipe> w;
+      w.voff_codes = lane * UB;
+      w.lut_base = lds_addr(lut);
+      float m_run[G], l_run[G], z_run[kQuantV ? G : 1];
 #pragma unroll
-      for (int i = 0; i < NH; ++i) {
-        m_run[i] = kNegInf;
-        l_run[i] = 0.f;
+      for (int h = 0; h < G; ++h) {
+        m_run[h] = kNegInf;
+        l_run[h] = 0.f;
+        if constexpr (kQuantV) z_run[h] = 0.f;
       }
-      const uint32_t voff_vpar = col * 4;
-
-      // descriptors of the pair's k-th page: codes, radius parameters, value parameters (rvp: the
-      // {fp16 scale, fp16 zero} of its valid tokens, with quantized values)
-      auto page_setup = [&](int k, __amdgpu_buffer_rsrc_t& rc, __amdgpu_buffer_rsrc_t& rp, __amdgpu_buffer_rsrc_t& rvp,
-                            int& nv) {
+      auto page_setup = [&](int k, __amdgpu_buffer_rsrc_t& rc, const uint32_t*& pp, __amdgpu_buffer_rsrc_t& rvp, int& nv) {
         const int pid = pids.get(k, lane);
         const bool ok = pid >= 0;
-        const int64_t ph = ok ? static_cast<int64_t>(pid) * a.n_kv_heads + kvh : 0;
+        const int64_t ph = (ok ? static_cast<int64_t>(pid) : 0) * a.n_kv_heads + kvh;
         nv = ok ? min(kGroup, L - (page0 + pair + kPairsOfWaves * k) * kGroup) : 0;
         const bool packed = ok && (page0 + pair + kPairsOfWaves * k) != res_page;
         rc = make_rsrc(a.codes + ph * kCodesBytes, packed ? kCodesBytes : 0u);
-        rp = make_rsrc(a.params + ph * kPairs, packed ? kPairs * 4u : 0u);
+        pp = a.params + ph * kPairs;                     // valid memory also for a masked page (pool page 0, unused)
         if constexpr (kQuantV) rvp = make_rsrc(a.v_params + ph * kGroup, static_cast<uint32_t>(nv) * 4u);
-        else rvp = rp;
+        else rvp = rc;
       };
-
-      // the first page's parameters and codes are under way while the table is built
-      __amdgpu_buffer_rsrc_t rc_cur, rp_cur, rvp_cur, rc_nxt, rp_nxt, rvp_nxt;
+      __amdgpu_buffer_rsrc_t rc_cur, rvp_cur, rc_nxt, rvp_nxt;
+      const uint32_t* pp_cur;
+      const uint32_t* pp_nxt;
       int nv_cur, nv_nxt;
-      page_setup(0, rc_cur, rp_cur, rvp_cur, nv_cur);
-      uint4 praw[4];
-      uint32_t vpar[8];                                              // quantized values: (scale, zero) of tokens 16 t + col
-      Unit<W / 2> cu[8];
+      page_setup(0, rc_cur, pp_cur, rvp_cur, nv_cur);
+      uint32_t vpar[2];                                              // quantized values: (scale, zero) of tokens lane, 64 + lane
 #pragma unroll
-      for (int i = 0; i < 4; ++i) praw[i] = buf_load16<kAuxCached>(rp_cur, voff_params, i * 16);
+      for (int b = 0; b < kBlocks; ++b) w.par[b] = load_block_params(pp_cur, b);
       if constexpr (kQuantV) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t) vpar[t] = buf_load4<kAuxCached>(rvp_cur, voff_vpar, t * 64);
+        for (int half = 0; half < 2; ++half) vpar[half] = buf_load4<kAuxCached>(rvp_cur, lane * 4, half * 256);
       }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) cu[i] = load_unit<W>(rc_cur, voff_codes, i * 16 * UB);
+      for (int b = 0; b < kBlocks; ++b)
+#pragma unroll
+        for (int half = 0; half < 2; ++half) w.cu[half * kBlocks + b] = load_unit<W>(rc_cur, w.voff_codes, w.unit_at(half, b));
 
       store_query_lds<G>(q_lds, trig, q_regs, tid);
       __syncthreads();
@@ -213,7 +219,7 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
       for (int i = 0; i < NH; ++i) build_uniform_table<TB>(lut + i * (kPairs * ROW), q_lds + i * kHeadDim, trig, tid, kRoleThreads);
       __syncthreads();
 
-      // residual group (plain dot products), if this pair owns its page
+      // residual group (plain dot products, in the lane layout of the other score path), if this pair owns its page
       if (res_page >= page0 + pair && res_page < page0 + npg && ((res_page - page0 - pair) % kPairsOfWaves) == 0) {
         residual_scores<G>(a.residual + (static_cast<int64_t>(seq) * a.n_kv_heads + kvh) * (kGroup * kHeadDim),
                            L - res_page * kGroup, lds_addr(q_lds), row, col, [&](int s, Folded<G> v) {
@@ -228,95 +234,94 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
         if constexpr (BAL) rotate_priority(tier + t);
         if (t < n_p) {
           const int pi = page0 + pair + kPairsOfWaves * t;
-          page_setup(t + 1, rc_nxt, rp_nxt, rvp_nxt, nv_nxt);
-          float sf[16], zz[16];
-          unpack_radius_params(praw, sf, zz);
-#pragma unroll
-          for (int v4 = 0; v4 < 4; ++v4) praw[v4] = buf_load16<kAuxCached>(rp_nxt, voff_params, v4 * 16);
-          float sc[NH][8];
-#pragma unroll
-          for (int s = 0; s < 8; ++s) {
-            float part[G];
-#pragma unroll
-            for (int h = 0; h < G; ++h) part[h] = 0.f;
-            score_steps<G, RB, TB, 0>(cu[s], lut_row0, sf, zz, part);
-            cu[s] = load_unit<W>(rc_nxt, voff_codes, s * 16 * UB);       // the pair's next page, same pass
-            const Folded<G> f = fold_rows<G>(part);
-#pragma unroll
-            for (int i = 0; i < NH; ++i) sc[i][s] = f.v[i];
-          }
-          if (pi == res_page) {
-#pragma unroll
-            for (int i = 0; i < NH; ++i)
-#pragma unroll
-              for (int s = 0; s < 8; ++s)
-                sc[i][s] = *(const PQ_LDS float*)static_cast<uintptr_t>(lds_addr(res_sc) + ((s * 16 + col) * G + my_head + 4 * i) * 4);
-          }
-          // online softmax (log2 domain); probabilities and rescaling factor go to buffer t % 2
+          page_setup(t + 1, rc_nxt, pp_nxt, rvp_nxt, nv_nxt);
+          w.run(rc_nxt, pp_nxt);
           const uint32_t pw = lds_addr(prob[pair][t & 1]);
+          float al[G];
+          uint32_t packed[kPairP ? 2 : 1][G];                        // fp16 probability pairs of this lane, per half
+          float pf[kPairP ? 1 : 2][G];                               // fp32 probabilities of this lane's two tokens
 #pragma unroll
-          for (int i = 0; i < NH; ++i) {
-            const int head = my_head + 4 * i;
-            float pm = kNegInf;
+          for (int h = 0; h < G; ++h) {
+            float sc[2];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-              const int tok = k * 16 + col;
+            for (int half = 0; half < 2; ++half) {
+              const int tok = half * 64 + lane;
+              sc[half] = w.score[half][h];
+              if (pi == res_page) sc[half] = *(const PQ_LDS float*)static_cast<uintptr_t>(lds_addr(res_sc) + (tok * G + h) * 4);
               if (a.scores != nullptr) {
-                if (owner && tok < nv_cur)
-                  a.scores[(static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0 + head) * a.scores_stride +
-                           static_cast<int64_t>(pi) * kGroup + tok] = sc[i][k];
+                if (tok < nv_cur)
+                  a.scores[(static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0 + h) * a.scores_stride +
+                           static_cast<int64_t>(pi) * kGroup + tok] = sc[half];
               }
-              sc[i][k] = (tok < nv_cur) ? sc[i][k] * a.scale_log2 : kNegInf;
-              pm = fmaxf(pm, sc[i][k]);
+              sc[half] = (tok < nv_cur) ? sc[half] * a.scale_log2 : kNegInf;
             }
-            pm = row_max(pm);
-            const float m_new = fmaxf(m_run[i], pm);
+            const float pm = wave_max(fmaxf(sc[0], sc[1]));
+            const float m_new = fmaxf(m_run[h], pm);
             const bool dead = !(m_new > kNegInf);
-            const float alpha = dead ? 1.f : __builtin_amdgcn_exp2f(m_run[i] - m_new);
+            const float alpha = dead ? 1.f : __builtin_amdgcn_exp2f(m_run[h] - m_new);
             float psum = 0.f, zsum = 0.f;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-              const float p = dead ? 0.f : __builtin_amdgcn_exp2f(sc[i][k] - m_new);
-              psum += p;
+            for (int half = 0; half < 2; ++half) {
+              const float pr = dead ? 0.f : __builtin_amdgcn_exp2f(sc[half] - m_new);
+              psum += pr;
               if constexpr (kQuantV) {
-                // V~ = code * s + z (Section 2): fold s into the probability, collect p * z; the
-                // probabilities of tokens 2m, 2m + 1 (neighbour lanes) go over as one fp16 pair
-                const __half2 sz = *reinterpret_cast<const __half2*>(&vpar[k]);
-                zsum = fmaf(p, __high2float(sz), zsum);
-                const uint32_t pr = pack_with_neighbour(p * __low2float(sz));
-                if (owner && (col & 1) == 0)
-                  *(PQ_LDS uint32_t*)static_cast<uintptr_t>(pw + ((k * 8 + (col >> 1)) * G + head) * 4) = pr;
+                // V~ = code * s + z (Section 2): fold s into the probability, collect p * z; tokens
+                // 2m, 2m + 1 (neighbour lanes) go over as one fp16 pair
+                const __half2 sz = *reinterpret_cast<const __half2*>(&vpar[half]);
+                zsum = fmaf(pr, __high2float(sz), zsum);
+                packed[half][h] = pack_with_neighbour(pr * __low2float(sz));
               } else if constexpr (G == 8) {
-                // tokens n and n + 4 (lanes col, col + 4) as one fp16 pair: they are rows of two
-                // consecutive value loads of the same lane (pair index: 8 per pass of 16 tokens)
-                const uint32_t pr = pack_with_lane4(p);
-                if ((col & 4) == 0)
-                  *(PQ_LDS uint32_t*)static_cast<uintptr_t>(pw + ((k * 8 + (col & 3) + ((col >> 3) << 2)) * G + head) * 4) = pr;
+                packed[half][h] = pack_with_lane4(pr);            // tokens n and n + 4 (lanes col, col + 4)
               } else {
-                if (owner) *(PQ_LDS float*)static_cast<uintptr_t>(pw + ((k * 16 + col) * G + head) * 4) = p;
+                pf[half][h] = pr;
               }
             }
-            if constexpr (kQuantV) z_run = fmaf(z_run, alpha, zsum);
-            l_run[i] = fmaf(l_run[i], alpha, psum);
-            m_run[i] = m_new;
-            if (owner && col == 0) alpha_s[pair][t & 1][head] = alpha;
+            if constexpr (kQuantV) z_run[h] = fmaf(z_run[h], alpha, zsum);
+            l_run[h] = fmaf(l_run[h], alpha, psum);
+            m_run[h] = m_new;
+            al[h] = alpha;
+          }
+          // the lane's probabilities, all heads of a token (pair) side by side
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            const int tok = half * 64 + lane;
+            if constexpr (kQuantV) {
+              if ((lane & 1) == 0) {
+#pragma unroll
+                for (int h = 0; h < G; ++h) *(PQ_LDS uint32_t*)static_cast<uintptr_t>(pw + ((tok >> 1) * G + h) * 4) = packed[half][h];
+              }
+            } else if constexpr (G == 8) {
+              // pair index of tokens (n, n + 4): 8 per pass of 16 tokens
+              if ((col & 4) == 0) {
+                const int pidx = (tok >> 4) * 8 + (col & 3) + ((col >> 3) << 2);
+#pragma unroll
+                for (int h = 0; h < G; ++h) *(PQ_LDS uint32_t*)static_cast<uintptr_t>(pw + (pidx * G + h) * 4) = packed[half][h];
+              }
+            } else {
+#pragma unroll
+              for (int h = 0; h < G; ++h) *(PQ_LDS float*)static_cast<uintptr_t>(pw + (tok * G + h) * 4) = pf[half][h];
+            }
+          }
+          if (lane == 0) {
+#pragma unroll
+            for (int h = 0; h < G; ++h) alpha_s[pair][t & 1][h] = al[h];
           }
           if constexpr (kQuantV) {
 #pragma unroll
-            for (int k = 0; k < 8; ++k) vpar[k] = buf_load4<kAuxCached>(rvp_nxt, voff_vpar, k * 64);
+            for (int half = 0; half < 2; ++half) vpar[half] = buf_load4<kAuxCached>(rvp_nxt, lane * 4, half * 256);
           }
-          rc_cur = rc_nxt; rp_cur = rp_nxt; rvp_cur = rvp_nxt; nv_cur = nv_nxt;
+          rc_cur = rc_nxt; pp_cur = pp_nxt; rvp_cur = rvp_nxt; nv_cur = nv_nxt;
         }
         __syncthreads();                                               // hand buffer t % 2 to the value wavefront
       }
-      const float z_tot = kQuantV ? row_sum(z_run) : 0.f;
 #pragma unroll
-      for (int i = 0; i < NH; ++i) {
-        const float l_tot = row_sum(l_run[i]);
-        if (owner && col == 0) {
-          red_ml[pair][my_head + 4 * i][0] = m_run[i];
-          red_ml[pair][my_head + 4 * i][1] = l_tot;
-          red_ml[pair][my_head + 4 * i][2] = z_tot;
+      for (int h = 0; h < G; ++h) {
+        const float l_tot = wave_sum_f(l_run[h]);
+        const float z_tot = kQuantV ? wave_sum_f(z_run[kQuantV ? h : 0]) : 0.f;
+        if (lane == 0) {
+          red_ml[pair][h][0] = m_run[h];
+          red_ml[pair][h][1] = l_tot;
+          red_ml[pair][h][2] = z_tot;
         }
       }
     } else {
