@@ -691,6 +691,227 @@ __device__ __forceinline__ void build_group_table(uint32_t lut_w, uint32_t tpar,
   }
 }
 
+// ---- score phase with lanes as tokens (uniform angle grid) ---------------------------------
+// Used by the score-only kernel and the role-specialised attention kernel.  (In the attention
+// kernel below, whose wavefronts alternate between scoring and aggregating, it measured the same
+// as the lane layout that kernel has -- 158 against 157 us with 4-bit values at the GQA shape --
+// and was not taken over.)  The lanes of a wavefront are 64 consecutive TOKENS of
+// a page and walk the 64 pairs together, block of 16 pairs by block, both halves of the page per
+// block.  Because all lanes read the same pair's table row (16 bytes per angle state, at most
+// 512 bytes: every LDS bank at most once, equal states broadcast), the gather is free of bank
+// conflicts whatever the codes are; the pair's radius parameters are wavefront-uniform and come
+// through scalar loads, one block (64 bytes) at a time, each block replaced by the next page's
+// as soon as it has been used.  Per pair and token: the field extraction, one conversion, one
+// multiply-add for the radius, G for the heads.
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+#define PQ_CONST __attribute__((address_space(4)))
+struct BlockParams {
+  uint32_t sz[16];     // {fp16 s, fp16 z} of the block's 16 pairs
+};
+// `page_params` is wavefront-uniform and points to valid memory
+__device__ __forceinline__ BlockParams load_block_params(const uint32_t* page_params, int block) {
+  const u32x16 v = *reinterpret_cast<const PQ_CONST u32x16*>(reinterpret_cast<uintptr_t>(page_params + block * kPairsPerUnit));
+  BlockParams p;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) p.sz[i] = v[i];
+  return p;
+}
+
+// A page's 128 steps of a lane -- step S: pair block kBlockOrder[S / 32], half of the page
+// (S / 16) % 2, pair S % 16 of the block -- with the table reads kScorePipe steps ahead of their
+// use.  Written out step by step, each step closed for the instruction scheduler: under this
+// kernel's register budget the compiler otherwise issues one read, waits for it, and so on.  As
+// a block's last step goes by, its parameters are replaced by the next page's; as a unit's last
+// read is issued, the unit is replaced by the next page's.
+// The sum over the 64 pairs is associated exactly as in the attention kernels, where the four
+// 16-lane rows each sum one block and fold_rows adds (block 0 + block 2) + (block 1 + block 3):
+// a score from here equals, bit for bit, the one the attention kernels compute.
+template <int G, int RB, int TB, int kScorePipe = 4>
+struct PageWalk {
+  static constexpr int W = RB + TB;
+  static constexpr int UB = 2 * W;
+  static constexpr int ROW = 16 << TB;
+  static constexpr int kRing = kScorePipe + 1;   // reads in flight, plus the one in use
+  Unit<W / 2> cu[2 * kBlocks];                   // unit (half, block) at [half * kBlocks + block]
+  BlockParams par[kBlocks];
+  float zz[16];
+  float c[kRing];
+  Heads<G> t[kRing];
+  float cur[2][G], sum02[2][G], sum13[2][G];     // per half of the page: the running block, and the pairs of blocks
+  float score[2][G];
+  uint32_t lut_base, voff_codes;
+
+  static constexpr uint32_t unit_at(int half, int b) { return static_cast<uint32_t>((b * kGroup + half * 64) * UB); }
+  static constexpr int block_of(int S) { return ((S / 32) >> 1) | (((S / 32) & 1) << 1); }   // 0, 2, 1, 3
+
+  template <int S>
+  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rc_nxt) {
+    if constexpr (S < 128) {
+      constexpr int b = block_of(S), half = (S / 16) % 2, K = S % 16;
+      uint32_t addr;
+      pair_fields<RB, TB, K>(cu[half * kBlocks + b], lut_base, c[S % kRing], addr);
+      t[S % kRing] = lut_read<G, kPairs * ROW>(addr + (b * kPairsPerUnit + K) * ROW);
+      if constexpr (K == 15) cu[half * kBlocks + b] = load_unit<W>(rc_nxt, voff_codes, unit_at(half, b));
+    }
+  }
+  template <int S>
+  __device__ __forceinline__ void steps(__amdgpu_buffer_rsrc_t rc_nxt, const uint32_t* pp_nxt) {
+    if constexpr (S < 128) {
+      constexpr int j = S / 32, b = block_of(S), half = (S / 16) % 2, K = S % 16;
+      if constexpr (S % 32 == 0) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) zz[k] = midpoint_offset(par[b].sz[k]);
+      }
+      issue<S + kScorePipe>(rc_nxt);
+      const float rho = radius_from_code(c[S % kRing], par[b].sz[K], zz[K]);
+#pragma unroll
+      for (int h = 0; h < G; ++h) cur[half][h] = fmaf(rho, t[S % kRing].v[h], K == 0 ? 0.f : cur[half][h]);
+      if constexpr (K == 15) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+          if constexpr (j == 0) sum02[half][h] = cur[half][h];
+          else if constexpr (j == 1) sum02[half][h] += cur[half][h];
+          else if constexpr (j == 2) sum13[half][h] = cur[half][h];
+          else score[half][h] = sum02[half][h] + (sum13[half][h] + cur[half][h]);
+        }
+      }
+      if constexpr (S % 32 == 31) par[b] = load_block_params(pp_nxt, b);
+      __builtin_amdgcn_sched_barrier(0);
+      steps<S + 1>(rc_nxt, pp_nxt);
+    }
+  }
+  // scores of the page in cu / par (left in `score`); cu / par then hold the next page
+  __device__ __forceinline__ void run(__amdgpu_buffer_rsrc_t rc_nxt, const uint32_t* pp_nxt) {
+    issue<0>(rc_nxt);
+    issue<1>(rc_nxt);
+    if constexpr (kScorePipe > 2) issue<2>(rc_nxt);
+    if constexpr (kScorePipe > 3) issue<3>(rc_nxt);
+    if constexpr (kScorePipe > 4) issue<4>(rc_nxt);
+    if constexpr (kScorePipe > 5) issue<5>(rc_nxt);
+    static_assert(kScorePipe >= 2 && kScorePipe <= 6, "reads in flight");
+    steps<0>(rc_nxt, pp_nxt);
+    // The scores exist here, whatever the caller's control flow does with them: left to itself
+    // the compiler moves a head's 64 multiply-adds behind a later condition under which the score
+    // is used, away from their table reads, whose results then wait in (spilled) registers.
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int h = 0; h < G; ++h) asm volatile("" : "+v"(score[half][h]));
+  }
+};
+
+// Online softmax (log2 domain) of a score wavefront whose lanes are tokens: the lane holds the raw
+// scores of tokens `lane` and 64 + `lane` of a page for all G heads (PageWalk::score), so a head's
+// maximum is a wavefront-wide reduction and its running maximum and rescaling factor are
+// uniform; the denominators stay per-lane partial sums until the end.  A page's probabilities go
+// to LDS at `pw` in the layout the value steps read:
+//   fp16 values, G <= 4 : fp32 [token][G]
+//   fp16 values, G == 8 : fp16 pairs of tokens (n, n + 4), [pair = 8 (n / 16) + n % 4 + 4 ((n % 16) / 8)][8]
+//   quantized values    : fp16 pairs of tokens (2m, 2m + 1) with the token's scale folded in, [m][G]
+// and the heads' rescaling factors to `alpha_out[0 .. G)`.
+template <int G, int VB>
+struct LaneSoftmax {
+  static constexpr bool kQuantV = VB != 16;
+  static constexpr bool kPairs16 = kQuantV || G == 8;       // probabilities leave as fp16 pairs
+  float m_run[G], l_run[G], z_run[kQuantV ? G : 1];
+
+  __device__ __forceinline__ void reset() {
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      m_run[h] = kNegInf;
+      l_run[h] = 0.f;
+      if constexpr (kQuantV) z_run[h] = 0.f;
+    }
+  }
+  // score[half][h]: raw scores; nv: valid tokens of the page; vpar[half]: {fp16 scale, fp16 zero} of
+  // the lane's tokens (quantized values).  `is_residual`: the page is the residual group, whose
+  // scores [token][G] are taken from LDS at `res_sc` instead.  `out_rows`: where to store raw scores
+  // (row of head 0 at the page's first token, rows `stride` apart), or null.
+  __device__ __forceinline__ void page(const float (&score)[2][G], int nv, float scale_log2, const uint32_t (&vpar)[2],
+                                       bool is_residual, uint32_t res_sc, float* out_rows, int64_t stride, uint32_t pw,
+                                       float* alpha_out, int lane) {
+    const int col = lane & 15;
+    float al[G];
+    uint32_t packed[kPairs16 ? 2 : 1][G];
+    float pf[kPairs16 ? 1 : 2][G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      float sc[2];
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int tok = half * 64 + lane;
+        sc[half] = score[half][h];
+        if (is_residual) sc[half] = *(const PQ_LDS float*)static_cast<uintptr_t>(res_sc + (tok * G + h) * 4);
+        if (out_rows != nullptr) {
+          if (tok < nv) out_rows[h * stride + tok] = sc[half];
+        }
+        sc[half] = (tok < nv) ? sc[half] * scale_log2 : kNegInf;
+      }
+      const float pm = wave_max(fmaxf(sc[0], sc[1]));
+      const float m_new = fmaxf(m_run[h], pm);
+      const bool dead = !(m_new > kNegInf);                          // nothing valid seen so far
+      const float alpha = dead ? 1.f : __builtin_amdgcn_exp2f(m_run[h] - m_new);   // 0 on the first page
+      float psum = 0.f, zsum = 0.f;
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const float pr = dead ? 0.f : __builtin_amdgcn_exp2f(sc[half] - m_new);
+        psum += pr;
+        if constexpr (kQuantV) {
+          // V~ = code * s + z (Section 2): fold s into the probability, collect p * z
+          const __half2 sz = *reinterpret_cast<const __half2*>(&vpar[half]);
+          zsum = fmaf(pr, __high2float(sz), zsum);
+          packed[half][h] = pack_with_neighbour(pr * __low2float(sz));
+        } else if constexpr (G == 8) {
+          packed[half][h] = pack_with_lane4(pr);
+        } else {
+          pf[half][h] = pr;
+        }
+      }
+      if constexpr (kQuantV) z_run[h] = fmaf(z_run[h], alpha, zsum);
+      l_run[h] = fmaf(l_run[h], alpha, psum);
+      m_run[h] = m_new;
+      al[h] = alpha;
+    }
+    // the lane's probabilities, all heads of a token (pair) side by side
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int tok = half * 64 + lane;
+      if constexpr (kQuantV) {
+        if ((lane & 1) == 0) {
+#pragma unroll
+          for (int h = 0; h < G; ++h) *(PQ_LDS uint32_t*)static_cast<uintptr_t>(pw + ((tok >> 1) * G + h) * 4) = packed[half][h];
+        }
+      } else if constexpr (G == 8) {
+        if ((col & 4) == 0) {
+          const int pidx = (tok >> 4) * 8 + (col & 3) + ((col >> 3) << 2);
+#pragma unroll
+          for (int h = 0; h < G; ++h) *(PQ_LDS uint32_t*)static_cast<uintptr_t>(pw + (pidx * G + h) * 4) = packed[half][h];
+        }
+      } else {
+#pragma unroll
+        for (int h = 0; h < G; ++h) *(PQ_LDS float*)static_cast<uintptr_t>(pw + (tok * G + h) * 4) = pf[half][h];
+      }
+    }
+    if (lane == 0) {
+#pragma unroll
+      for (int h = 0; h < G; ++h) alpha_out[h] = al[h];
+    }
+  }
+  // (m, l, sum of p * zero-point) of head h over everything this wavefront has seen, to ml[h][0..2]
+  __device__ __forceinline__ void finish(float (*ml)[3], int lane) {
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      const float l_tot = wave_sum_f(l_run[h]);
+      const float z_tot = kQuantV ? wave_sum_f(z_run[kQuantV ? h : 0]) : 0.f;
+      if (lane == 0) {
+        ml[h][0] = m_run[h];
+        ml[h][1] = l_tot;
+        ml[h][2] = z_tot;
+      }
+    }
+  }
+};
+
 template <int G, int RB, int TB, int VB, bool GA>
 __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
   constexpr int W = RB + TB;
@@ -1160,112 +1381,8 @@ __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArg
 }
 
 // ---- query-key scores only (the kernel the paper times in Section 5.2) ------------------
-// Uniform angle grid.  Same table as the attention kernels; the lanes of a wavefront are 64
-// consecutive TOKENS of a page and walk the 64 pairs together, block of 16 pairs by block, both
-// halves of the page per block.  Because all lanes read the same pair's table row (16 bytes per
-// angle state, at most 512 bytes: every LDS bank at most once, equal states broadcast), the
-// gather is free of bank conflicts whatever the codes are; the pair's radius parameters are
-// wavefront-uniform and come through scalar loads, one block (64 bytes) at a time, each block
-// replaced by the next page's as soon as it has been used; and a head's scores of 64 tokens leave
-// as whole cache lines.  Per pair and token: the field extraction, one conversion, one
-// multiply-add for the radius, G for the heads.
-typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
-#define PQ_CONST __attribute__((address_space(4)))
-struct BlockParams {
-  uint32_t sz[16];     // {fp16 s, fp16 z} of the block's 16 pairs
-};
-// `page_params` is wavefront-uniform and points to valid memory
-__device__ __forceinline__ BlockParams load_block_params(const uint32_t* page_params, int block) {
-  const u32x16 v = *reinterpret_cast<const PQ_CONST u32x16*>(reinterpret_cast<uintptr_t>(page_params + block * kPairsPerUnit));
-  BlockParams p;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) p.sz[i] = v[i];
-  return p;
-}
-
-// A page's 128 steps of a lane -- step S: pair block kBlockOrder[S / 32], half of the page
-// (S / 16) % 2, pair S % 16 of the block -- with the table reads kScorePipe steps ahead of their
-// use.  Written out step by step, each step closed for the instruction scheduler: under this
-// kernel's register budget the compiler otherwise issues one read, waits for it, and so on.  As
-// a block's last step goes by, its parameters are replaced by the next page's; as a unit's last
-// read is issued, the unit is replaced by the next page's.
-// The sum over the 64 pairs is associated exactly as in the attention kernels, where the four
-// 16-lane rows each sum one block and fold_rows adds (block 0 + block 2) + (block 1 + block 3):
-// a score from here equals, bit for bit, the one the attention kernels compute.
-template <int G, int RB, int TB, int kScorePipe = 4>
-struct PageWalk {
-  static constexpr int W = RB + TB;
-  static constexpr int UB = 2 * W;
-  static constexpr int ROW = 16 << TB;
-  static constexpr int kRing = kScorePipe + 1;   // reads in flight, plus the one in use
-  Unit<W / 2> cu[2 * kBlocks];                   // unit (half, block) at [half * kBlocks + block]
-  BlockParams par[kBlocks];
-  float zz[16];
-  float c[kRing];
-  Heads<G> t[kRing];
-  float cur[2][G], sum02[2][G], sum13[2][G];     // per half of the page: the running block, and the pairs of blocks
-  float score[2][G];
-  uint32_t lut_base, voff_codes;
-
-  static constexpr uint32_t unit_at(int half, int b) { return static_cast<uint32_t>((b * kGroup + half * 64) * UB); }
-  static constexpr int block_of(int S) { return ((S / 32) >> 1) | (((S / 32) & 1) << 1); }   // 0, 2, 1, 3
-
-  template <int S>
-  __device__ __forceinline__ void issue(__amdgpu_buffer_rsrc_t rc_nxt) {
-    if constexpr (S < 128) {
-      constexpr int b = block_of(S), half = (S / 16) % 2, K = S % 16;
-      uint32_t addr;
-      pair_fields<RB, TB, K>(cu[half * kBlocks + b], lut_base, c[S % kRing], addr);
-      t[S % kRing] = lut_read<G, kPairs * ROW>(addr + (b * kPairsPerUnit + K) * ROW);
-      if constexpr (K == 15) cu[half * kBlocks + b] = load_unit<W>(rc_nxt, voff_codes, unit_at(half, b));
-    }
-  }
-  template <int S>
-  __device__ __forceinline__ void steps(__amdgpu_buffer_rsrc_t rc_nxt, const uint32_t* pp_nxt) {
-    if constexpr (S < 128) {
-      constexpr int j = S / 32, b = block_of(S), half = (S / 16) % 2, K = S % 16;
-      if constexpr (S % 32 == 0) {
-#pragma unroll
-        for (int k = 0; k < 16; ++k) zz[k] = midpoint_offset(par[b].sz[k]);
-      }
-      issue<S + kScorePipe>(rc_nxt);
-      const float rho = radius_from_code(c[S % kRing], par[b].sz[K], zz[K]);
-#pragma unroll
-      for (int h = 0; h < G; ++h) cur[half][h] = fmaf(rho, t[S % kRing].v[h], K == 0 ? 0.f : cur[half][h]);
-      if constexpr (K == 15) {
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-          if constexpr (j == 0) sum02[half][h] = cur[half][h];
-          else if constexpr (j == 1) sum02[half][h] += cur[half][h];
-          else if constexpr (j == 2) sum13[half][h] = cur[half][h];
-          else score[half][h] = sum02[half][h] + (sum13[half][h] + cur[half][h]);
-        }
-      }
-      if constexpr (S % 32 == 31) par[b] = load_block_params(pp_nxt, b);
-      __builtin_amdgcn_sched_barrier(0);
-      steps<S + 1>(rc_nxt, pp_nxt);
-    }
-  }
-  // scores of the page in cu / par (left in `score`); cu / par then hold the next page
-  __device__ __forceinline__ void run(__amdgpu_buffer_rsrc_t rc_nxt, const uint32_t* pp_nxt) {
-    issue<0>(rc_nxt);
-    issue<1>(rc_nxt);
-    if constexpr (kScorePipe > 2) issue<2>(rc_nxt);
-    if constexpr (kScorePipe > 3) issue<3>(rc_nxt);
-    if constexpr (kScorePipe > 4) issue<4>(rc_nxt);
-    if constexpr (kScorePipe > 5) issue<5>(rc_nxt);
-    static_assert(kScorePipe >= 2 && kScorePipe <= 6, "reads in flight");
-    steps<0>(rc_nxt, pp_nxt);
-    // The scores exist here, whatever the caller's control flow does with them: left to itself
-    // the compiler moves a head's 64 multiply-adds behind a later condition under which the score
-    // is used, away from their table reads, whose results then wait in (spilled) registers.
-#pragma unroll
-    for (int half = 0; half < 2; ++half)
-#pragma unroll
-      for (int h = 0; h < G; ++h) asm volatile("" : "+v"(score[half][h]));
-  }
-};
-
+// Uniform angle grid: the token-lane walk (PageWalk) and nothing else -- every wavefront scores
+// its pages, and a head's scores of 64 tokens leave as whole cache lines.
 #ifndef PQ_SCORE_WAVES
 #define PQ_SCORE_WAVES 4
 #endif

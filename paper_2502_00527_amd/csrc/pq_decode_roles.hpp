@@ -178,13 +178,8 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
       PageWalk<G, RB, TB, kPipe> w;
       w.voff_codes = lane * UB;
       w.lut_base = lds_addr(lut);
-      float m_run[G], l_run[G], z_run[kQuantV ? G : 1];
-#pragma unroll
-      for (int h = 0; h < G; ++h) {
-        m_run[h] = kNegInf;
-        l_run[h] = 0.f;
-        if constexpr (kQuantV) z_run[h] = 0.f;
-      }
+      LaneSoftmax<G, VB> sm;
+      sm.reset();
       auto page_setup = [&](int k, __amdgpu_buffer_rsrc_t& rc, const uint32_t*& pp, __amdgpu_buffer_rsrc_t& rvp, int& nv) {
         const int pid = pids.get(k, lane);
         const bool ok = pid >= 0;
@@ -236,76 +231,11 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
           const int pi = page0 + pair + kPairsOfWaves * t;
           page_setup(t + 1, rc_nxt, pp_nxt, rvp_nxt, nv_nxt);
           w.run(rc_nxt, pp_nxt);
-          const uint32_t pw = lds_addr(prob[pair][t & 1]);
-          float al[G];
-          uint32_t packed[kPairP ? 2 : 1][G];                        // fp16 probability pairs of this lane, per half
-          float pf[kPairP ? 1 : 2][G];                               // fp32 probabilities of this lane's two tokens
-#pragma unroll
-          for (int h = 0; h < G; ++h) {
-            float sc[2];
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-              const int tok = half * 64 + lane;
-              sc[half] = w.score[half][h];
-              if (pi == res_page) sc[half] = *(const PQ_LDS float*)static_cast<uintptr_t>(lds_addr(res_sc) + (tok * G + h) * 4);
-              if (a.scores != nullptr) {
-                if (tok < nv_cur)
-                  a.scores[(static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0 + h) * a.scores_stride +
-                           static_cast<int64_t>(pi) * kGroup + tok] = sc[half];
-              }
-              sc[half] = (tok < nv_cur) ? sc[half] * a.scale_log2 : kNegInf;
-            }
-            const float pm = wave_max(fmaxf(sc[0], sc[1]));
-            const float m_new = fmaxf(m_run[h], pm);
-            const bool dead = !(m_new > kNegInf);
-            const float alpha = dead ? 1.f : __builtin_amdgcn_exp2f(m_run[h] - m_new);
-            float psum = 0.f, zsum = 0.f;
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-              const float pr = dead ? 0.f : __builtin_amdgcn_exp2f(sc[half] - m_new);
-              psum += pr;
-              if constexpr (kQuantV) {
-                // V~ = code * s + z (Section 2): fold s into the probability, collect p * z; tokens
-                // 2m, 2m + 1 (neighbour lanes) go over as one fp16 pair
-                const __half2 sz = *reinterpret_cast<const __half2*>(&vpar[half]);
-                zsum = fmaf(pr, __high2float(sz), zsum);
-                packed[half][h] = pack_with_neighbour(pr * __low2float(sz));
-              } else if constexpr (G == 8) {
-                packed[half][h] = pack_with_lane4(pr);            // tokens n and n + 4 (lanes col, col + 4)
-              } else {
-                pf[half][h] = pr;
-              }
-            }
-            if constexpr (kQuantV) z_run[h] = fmaf(z_run[h], alpha, zsum);
-            l_run[h] = fmaf(l_run[h], alpha, psum);
-            m_run[h] = m_new;
-            al[h] = alpha;
-          }
-          // the lane's probabilities, all heads of a token (pair) side by side
-#pragma unroll
-          for (int half = 0; half < 2; ++half) {
-            const int tok = half * 64 + lane;
-            if constexpr (kQuantV) {
-              if ((lane & 1) == 0) {
-#pragma unroll
-                for (int h = 0; h < G; ++h) *(PQ_LDS uint32_t*)static_cast<uintptr_t>(pw + ((tok >> 1) * G + h) * 4) = packed[half][h];
-              }
-            } else if constexpr (G == 8) {
-              // pair index of tokens (n, n + 4): 8 per pass of 16 tokens
-              if ((col & 4) == 0) {
-                const int pidx = (tok >> 4) * 8 + (col & 3) + ((col >> 3) << 2);
-#pragma unroll
-                for (int h = 0; h < G; ++h) *(PQ_LDS uint32_t*)static_cast<uintptr_t>(pw + (pidx * G + h) * 4) = packed[half][h];
-              }
-            } else {
-#pragma unroll
-              for (int h = 0; h < G; ++h) *(PQ_LDS float*)static_cast<uintptr_t>(pw + (tok * G + h) * 4) = pf[half][h];
-            }
-          }
-          if (lane == 0) {
-#pragma unroll
-            for (int h = 0; h < G; ++h) alpha_s[pair][t & 1][h] = al[h];
-          }
+          float* const out_rows = a.scores == nullptr ? nullptr
+              : a.scores + (static_cast<int64_t>(seq) * a.n_q_heads + kvh * a.group_total + a.head0) * a.scores_stride +
+                    static_cast<int64_t>(pi) * kGroup;
+          sm.page(w.score, nv_cur, a.scale_log2, vpar, pi == res_page, lds_addr(res_sc), out_rows, a.scores_stride,
+                  lds_addr(prob[pair][t & 1]), alpha_s[pair][t & 1], lane);
           if constexpr (kQuantV) {
 #pragma unroll
             for (int half = 0; half < 2; ++half) vpar[half] = buf_load4<kAuxCached>(rvp_nxt, lane * 4, half * 256);
@@ -314,16 +244,7 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
         }
         __syncthreads();                                               // hand buffer t % 2 to the value wavefront
       }
-#pragma unroll
-      for (int h = 0; h < G; ++h) {
-        const float l_tot = wave_sum_f(l_run[h]);
-        const float z_tot = kQuantV ? wave_sum_f(z_run[kQuantV ? h : 0]) : 0.f;
-        if (lane == 0) {
-          red_ml[pair][h][0] = m_run[h];
-          red_ml[pair][h][1] = l_tot;
-          red_ml[pair][h][2] = z_tot;
-        }
-      }
+      sm.finish(red_ml[pair], lane);
     } else {
       // =========================== VALUE wavefront ===========================
       const uint32_t voff_values = kQuantV ? lane * 16 : row * (kHeadDim * 2) + col * 16;
