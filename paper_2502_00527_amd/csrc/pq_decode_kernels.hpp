@@ -1084,7 +1084,17 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
     wave_lds_sync();
   }
 
+  // Two work-groups share a compute unit, and the SIMD favours the older wavefront among equal
+  // priorities: the two take the higher priority in turns, page by page (see rotate_priority in
+  // pq_decode_roles.hpp for the same effect there).
+  const unsigned launch_index = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  const bool shares_cu = gridDim.x * gridDim.y * gridDim.z > 256u;
+  const int turn0 = static_cast<int>((launch_index / 256u) & 1u);
   for (int i = 0; i < n_w; ++i) {
+    if (shares_cu) {
+      if ((turn0 + i) & 1) __builtin_amdgcn_s_setprio(1);
+      else __builtin_amdgcn_s_setprio(0);
+    }
     const int pi = page0 + wave + kWaves * i;                      // chunk-relative page of iteration i
     if (i + 1 < n_w) {
       page_setup(i + 1, rc_nxt, rp_nxt, rv_nxt, rvp_nxt, nv_nxt, rot_nxt);

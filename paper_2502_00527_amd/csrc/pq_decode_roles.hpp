@@ -77,13 +77,16 @@ struct PageIds {
   }
 };
 
-// Issue priority of this wavefront for one step.  The three work-groups resident on a compute
-// unit started one after the other, and among wavefronts of equal priority the SIMD favours the
+// Issue priority of this wavefront for one step.  The work-groups resident on a compute unit
+// started one after the other, and among wavefronts of equal priority the SIMD favours the
 // oldest: left alone, the first-started work-group of a compute unit finishes its (equal) share
-// ~15 % earlier than the last-started one, and the launch waits for the slowest.  Rotating the
-// priorities from step to step gives each of them the same turn.
-__device__ __forceinline__ void rotate_priority(int turn) {
-  switch (turn % 3) {
+// 15-18 % earlier than the last-started one, and the launch waits for the slowest.  Rotating the
+// priorities from step to step, with the period of the number of work-groups that share the
+// compute unit (3 in balanced launches; 1-3 in grid launches, by their size), gives each of them
+// the same turn.
+__device__ __forceinline__ void rotate_priority(int turn, int period) {
+  const int p = period == 3 ? turn % 3 : (period == 2 ? (turn & 1) : 0);
+  switch (p) {
     case 0: __builtin_amdgcn_s_setprio(0); break;
     case 1: __builtin_amdgcn_s_setprio(1); break;
     default: __builtin_amdgcn_s_setprio(2); break;
@@ -136,7 +139,10 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
   const int pair = wave % kPairsOfWaves;      // which share of a segment's pages
   const bool scorer = wave < kPairsOfWaves;   // role of this wavefront
   constexpr uint32_t kCodesBytes = kBlocks * kGroup * UB;
-  const int tier = static_cast<int>(blockIdx.x * 3u / gridDim.x);   // 0, 1, 2 in start order on a compute unit
+  // start order on a compute unit (work-groups go round the 256 compute units) and how many share one
+  const int period = BAL ? 3 : min(3, static_cast<int>((gridDim.x + 255u) / 256u));
+  const int tier = BAL ? static_cast<int>(blockIdx.x * 3u / gridDim.x)
+                       : static_cast<int>((blockIdx.x / 256u) % static_cast<unsigned>(period));
   WorkSpan span;
   Segment seg;
   bool more;
@@ -226,7 +232,7 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
       }
 
       for (int t = 0; t < n_steps; ++t) {
-        if constexpr (BAL) rotate_priority(tier + t);
+        rotate_priority(tier + t, period);
         if (t < n_p) {
           const int pi = page0 + pair + kPairsOfWaves * t;
           page_setup(t + 1, rc_nxt, pp_nxt, rvp_nxt, nv_nxt);
@@ -292,7 +298,7 @@ void pq_decode_roles_kernel(const DecodeArgs a) {
       __syncthreads();
 
       for (int t = 0; t < n_steps; ++t) {
-        if constexpr (BAL) rotate_priority(tier + t);
+        rotate_priority(tier + t, period);
         const int j = t - 1;                                           // the page the score wavefront finished last step
         if (j >= 0 && j < n_p) {
           page_setup(j + 1, rv_nxt, rot_nxt);
