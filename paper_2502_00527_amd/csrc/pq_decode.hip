@@ -133,6 +133,10 @@ constexpr int kBalancedMinPages = PQ_BALANCED_MIN_PAGES;   // smallest share of 
 #define PQ_BALANCED_UNIT_COST 2
 #endif
 constexpr int kBalancedUnitCost = PQ_BALANCED_UNIT_COST;   // pages' worth of time to start on a (sequence, KV head)
+#ifndef PQ_BALANCED_XCD_SKEW
+#define PQ_BALANCED_XCD_SKEW 30
+#endif
+constexpr int kBalancedXcdSkewPermille = PQ_BALANCED_XCD_SKEW;   // even-numbered work-groups (even XCDs) take 3 % more, odd ones 3 % less
 constexpr int kBalancedMaxSeqs = 4096;       // every work-group scans all sequence lengths
 
 // Work-groups of a balanced launch: all that are resident at once (3 per compute unit), fewer if
@@ -325,6 +329,7 @@ int decode_launch(const pq_layout* layout, const void* q, pq_dtype q_dtype, int3
   a.arrivals = ws.arrivals;
   a.min_pages = kBalancedMinPages;
   a.unit_cost = kBalancedUnitCost;
+  a.xcd_skew_permille = kBalancedXcdSkewPermille;
   a.scores_stride = scores_stride;
   a.n_pool_pages = n_pool_pages;
   a.n_kv_heads = layout->n_kv_heads;

@@ -70,6 +70,7 @@ struct DecodeArgs {
   uint64_t* arrivals;       // one arrival word per (sequence, KV head), then one per segment slot
   int32_t min_pages;        // smallest share of a work-group, in pages
   int32_t unit_cost;        // what starting on a (sequence, KV head) costs a work-group, in pages
+  int32_t xcd_skew_permille;  // how much more than the average share an even-numbered work-group takes
   int32_t q_is_f32;         // the query is fp32 (else fp16)
   int32_t grid_mode;        // role-specialised kernel: one work-group per (KV head, sequence, chunk) instead
   int64_t scores_stride;

@@ -35,7 +35,8 @@ struct Segment {
 
 struct WorkSpan {
   int f, f1;           // next position of the line to hand out, end of this work-group's share
-  int per;             // positions per work-group
+  int per;             // positions per work-group, on average
+  int per_even;        // positions of an even-numbered work-group (the odd one after it takes 2 per - per_even)
   int seq, kvh, pos;   // where position f lies: unit and position inside it (overhead positions first)
   int n_pages;         // pages of sequence `seq`
   int L;
@@ -97,8 +98,15 @@ __device__ __forceinline__ void span_begin(const DecodeArgs& a, int lane, bool z
   }
   const int total = uni(wave_sum(mine)) * a.n_kv_heads;
   w.per = uni(max(a.min_pages + c, (total + n_wg - 1) / n_wg));
-  const int64_t f0 = static_cast<int64_t>(wg) * w.per;
-  w.f1 = uni(static_cast<int>(min<int64_t>(total, f0 + w.per)));
+  // Work-groups go round the XCDs in launch order, and with the memory system saturated the
+  // odd-numbered XCDs of an MI355X stream 7-10 % slower than the even-numbered ones (measured
+  // with time stamps per work-group, on every machine tried): of each pair of consecutive
+  // work-groups the even one takes the larger part, so that the two finish together.
+  int skew = (n_wg & 1) == 0 ? (w.per * a.xcd_skew_permille + 500) / 1000 : 0;
+  skew = max(0, min(skew, w.per - (a.min_pages + c)));
+  w.per_even = uni(w.per + skew);
+  const int64_t f0 = static_cast<int64_t>(wg >> 1) * (2 * w.per) + ((wg & 1) ? w.per_even : 0);
+  w.f1 = uni(static_cast<int>(min<int64_t>(total, f0 + ((wg & 1) ? 2 * w.per - w.per_even : w.per_even))));
   w.f = uni(static_cast<int>(min<int64_t>(total, f0)));
   w.seq = w.kvh = w.pos = w.n_pages = w.L = 0;
   if (w.f >= w.f1) return;
@@ -127,6 +135,13 @@ __device__ __forceinline__ void span_begin(const DecodeArgs& a, int lane, bool z
   w.f1 = w.f;   // not reached: position f < total always lies in some sequence
 }
 
+// The work-group whose share holds position x of the line.
+__device__ __forceinline__ int share_of(const WorkSpan& w, int x) {
+  const int two = 2 * w.per;
+  const int pair = x / two;
+  return 2 * pair + (x - pair * two >= w.per_even ? 1 : 0);
+}
+
 // Next segment of the share; false when the share is used up.
 __device__ __forceinline__ bool next_segment(const DecodeArgs& a, WorkSpan& w, Segment& seg) {
   const int c = a.unit_cost;
@@ -143,8 +158,8 @@ __device__ __forceinline__ bool next_segment(const DecodeArgs& a, WorkSpan& w, S
     seg.L = w.L;
     seg.npg = min(w.n_pages - seg.page0, w.f1 - w.f);
     const int first_page_at = w.f - seg.page0;     // position of the unit's page 0
-    seg.first_wg = uni(first_page_at / w.per);
-    seg.n_segs = uni((first_page_at + w.n_pages - 1) / w.per) - seg.first_wg + 1;
+    seg.first_wg = uni(share_of(w, first_page_at));
+    seg.n_segs = uni(share_of(w, first_page_at + w.n_pages - 1)) - seg.first_wg + 1;
     w.f += seg.npg;
     w.pos += seg.npg;
     if (w.pos == c + w.n_pages && w.f < w.f1) {
