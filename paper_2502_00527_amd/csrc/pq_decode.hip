@@ -152,14 +152,12 @@ AttentionKernel choose_attention_kernel(const pq_layout* l, int32_t v_bits, int3
                                         int32_t max_seq_len) {
   const int64_t max_pages = (static_cast<int64_t>(max_seq_len) + kGroup - 1) / kGroup;
   const int64_t bound = static_cast<int64_t>(n_seqs) * l->n_kv_heads * (max_pages + kBalancedUnitCost);
-  // Quantized values make the launch arithmetic-bound, and with 4 query heads per KV head most of
-  // that arithmetic is scoring: wavefronts that all score and aggregate use the four SIMDs evenly,
-  // specialised ones leave two of them short (measured at the GQA shape, 4-bit values: 150 against
-  // 178 us; with 1 or 2 heads per KV head the specialised kernel wins, 61 against 64 us at the MHA shape).
-#ifndef PQ_ROLES_VQ_MAX_GROUP
-#define PQ_ROLES_VQ_MAX_GROUP 2
-#endif
-  const bool roles_fit = v_bits == 16 || n_q_heads / l->n_kv_heads <= PQ_ROLES_VQ_MAX_GROUP;
+  // Quantized values make the launch arithmetic-bound, and with 4 query heads per KV head the
+  // value wavefront's unpacking and dot products are the longer side of every step of the
+  // specialised kernel: wavefronts that all score and aggregate use the four SIMDs evenly
+  // (measured at the GQA shape, 4-bit values: 147 against 166 us; with 2 heads per KV head the
+  // specialised kernel wins, 127 against 147 us).
+  const bool roles_fit = v_bits == 16 || n_q_heads / l->n_kv_heads <= 2;
   if (l->angle_quantizer == PQ_ANGLE_UNIFORM && roles_fit && n_seqs <= kBalancedMaxSeqs &&
       bound < (int64_t{1} << 31) && balanced_groups(l, n_seqs, max_seq_len) >= 256)
     return AttentionKernel::kRoles;
