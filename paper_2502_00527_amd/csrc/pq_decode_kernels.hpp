@@ -1277,6 +1277,7 @@ __global__ PQ_KERNEL_ATTR void pq_decode_partials_kernel(const DecodeArgs a) {
 // uniform grid is served by pq_score_tokens_kernel below; GA = false is not instantiated.)
 template <int G, int RB, int TB, bool GA>
 __global__ __launch_bounds__(kThreads) void pq_score_keys_kernel(const DecodeArgs a) {
+  static_assert(GA, "the uniform grid is served by pq_score_tokens_kernel");
   constexpr int W = RB + TB;
   constexpr int UB = 2 * W;
   constexpr int NA = 1 << TB;
